@@ -1,0 +1,331 @@
+"""CPU oracle for the DWDP MoE-layer hot path.  TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, obviously-correct numpy implementation of what one rank's MoE
+layer computes: router top-k, permutation by expert, block-scaled FP8 (or bf16)
+expert MLP with SwiGLU, weighted combine.  Floating point is fp64 unless a step
+fixes a precision (stated at the step).  Only tests, the smoke check and the
+benchmark's cpu_baseline leg may import this package; it shares no code with the
+HIP path and never imports it.
+
+Where the definitions come from.  The paper (Section 2, "Methodology Overview";
+Section 4.2, "Eliminating Split-Weight Merge Overhead") fixes *where* expert
+weights live and that the grouped GEMM reads them from several buffers; it
+delegates the MoE arithmetic itself to the DeepSeek-V3/R1 architecture
+(Section 5.1, "Hardware, Software Stack, and Model").  The arithmetic below is
+therefore the public DeepSeek-V3 MoE definition with the readings listed per
+function.  The buffer placement does not change the function computed, so the
+oracle takes each expert's weights by value.
+
+Parity pins (tests/test_oracle_*.py): brute-force per-token selection, closed
+forms for the e4m3 codec, library softmax / matmul special cases, permutation
+invariants, dense-sum identity for combine.  The absolute MoE output values have
+no printed worked example in the paper: "parity unpinned" by the paper for
+moe_forward's numeric output, pinned only by the identities above.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+SCORE_SOFTMAX = 0
+SCORE_SIGMOID = 1
+W_BF16 = 0
+W_FP8 = 1
+
+
+@dataclass(frozen=True)
+class LayerSpec:
+    """Routing and shape parameters of the layer (the oracle's own copy of the config)."""
+    H: int
+    I: int
+    E: int
+    K: int
+    n_group: int = 1
+    topk_group: int = 1
+    has_shared: int = 0
+    score_fn: int = SCORE_SOFTMAX
+    routed_scale: float = 1.0
+    w_dtype: int = W_BF16
+
+
+def spec_from(cfg) -> LayerSpec:
+    """Build a LayerSpec from any object with the same attribute names."""
+    return LayerSpec(H=cfg.H, I=cfg.I, E=cfg.E, K=cfg.K, n_group=cfg.n_group, topk_group=cfg.topk_group,
+                     has_shared=cfg.has_shared, score_fn=cfg.score_fn, routed_scale=cfg.routed_scale,
+                     w_dtype=cfg.w_dtype)
+
+
+# --------------------------------------------------------------------------------------
+# FP8 e4m3 (OCP "fn" variant: 4 exponent bits, bias 7, 3 mantissa bits, no infinities,
+# S.1111.111 = NaN, largest finite 448).  Written from the format definition.
+# --------------------------------------------------------------------------------------
+
+def e4m3_decode(code: int) -> float:
+    """Value of one e4m3 byte."""
+    sign = -1.0 if (code & 0x80) else 1.0
+    exp = (code >> 3) & 0xF
+    man = code & 0x7
+    if exp == 0xF and man == 0x7:
+        return math.nan
+    if exp == 0:
+        return sign * (man / 8.0) * 2.0 ** -6
+    return sign * (1.0 + man / 8.0) * 2.0 ** (exp - 7)
+
+
+E4M3_TABLE = np.array([e4m3_decode(c) for c in range(256)], dtype=np.float64)
+# The 127 finite non-negative values in increasing order (codes 0x00..0x7E).
+_E4M3_POS = E4M3_TABLE[:127].copy()
+
+
+def e4m3_encode(v: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even onto the e4m3 grid, saturating at +-448.  Returns uint8 codes.
+
+    Nearest grid point by search over the sorted table; an exact midpoint goes to the
+    neighbour with even code (even mantissa), which is IEEE round-half-even.
+    """
+    v = np.asarray(v, dtype=np.float64)
+    a = np.minimum(np.abs(v), 448.0)
+    hi = np.searchsorted(_E4M3_POS, a, side="left")          # first grid value >= a
+    hi = np.minimum(hi, 126)
+    lo = np.maximum(hi - 1, 0)
+    d_lo = a - _E4M3_POS[lo]
+    d_hi = _E4M3_POS[hi] - a
+    pick_hi = (d_hi < d_lo) | ((d_hi == d_lo) & (hi % 2 == 0))
+    code = np.where(pick_hi, hi, lo).astype(np.uint8)
+    neg = np.signbit(v)
+    return np.where(neg, code | 0x80, code).astype(np.uint8)
+
+
+def qdq_act(v: np.ndarray, group: int = 128) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Dynamic activation quantisation, per row and per `group` contiguous elements.
+
+    Decision precision is fp32 (the precision the kernels use for it): v is taken as fp32,
+    scale = fp32(amax) / fp32(448) (1.0 when the group is all zero), q = fp32(v / scale),
+    code = RNE e4m3(q).  Returns (dequantised fp64 values, uint8 codes, fp32 scales [rows, n/group]).
+    """
+    v32 = np.asarray(v, dtype=np.float32)
+    rows, n = v32.shape
+    assert n % group == 0
+    g = v32.reshape(rows, n // group, group)
+    amax = np.abs(g).max(axis=2)
+    scale = np.where(amax > 0, amax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+    q = (g / scale[:, :, None]).astype(np.float32)
+    codes = e4m3_encode(q)
+    deq = E4M3_TABLE[codes] * scale[:, :, None].astype(np.float64)
+    return deq.reshape(rows, n), codes.reshape(rows, n), scale
+
+
+def dequant_blocks(codes: np.ndarray, scales: np.ndarray, block: int = 128) -> np.ndarray:
+    """fp64 matrix from e4m3 bytes [R,C] and fp32 scales [R/block, C/block]."""
+    R, C = codes.shape
+    w = E4M3_TABLE[codes]
+    s = np.repeat(np.repeat(scales.astype(np.float64), block, axis=0), block, axis=1)
+    return w * s[:R, :C]
+
+
+# --------------------------------------------------------------------------------------
+# Router
+# --------------------------------------------------------------------------------------
+
+def _argsort_desc_stable(c: np.ndarray) -> np.ndarray:
+    """Indices by descending value; equal values keep the lower index first."""
+    return np.argsort(-c, kind="stable")
+
+
+def route(logits: np.ndarray, bias: Optional[np.ndarray], spec: LayerSpec):
+    """Router top-k.  Returns (topk_ids int32 [T,K], topk_w fp32 [T,K]).
+
+    Sigmoid scoring (DeepSeek-V3 style):
+      s_e = fp32( 1 / (1 + exp(-fp64(z_e))) )      evaluated in fp64, rounded once
+      c_e = fp32(s_e + b_e)                        selection score; the bias only selects
+      group score = fp32 sum of the two largest c_e of the group (groups = contiguous E/n_group)
+      keep the topk_group best groups, then the K best c_e among their experts
+      w_k = s_{e_k} / (sum_j s_{e_j} + 1e-20) * routed_scale        (un-biased scores)
+    Softmax scoring: selection on the raw logits (softmax is monotone), no bias, and
+      w = softmax over the K selected logits times routed_scale (equal to the full softmax
+      renormalised over the selection).
+    Ties go to the lower expert / group index; ids are listed by descending selection score.
+    """
+    z = np.asarray(logits, dtype=np.float32)
+    T, E = z.shape
+    assert E == spec.E
+    K = spec.K
+    ids = np.zeros((T, K), dtype=np.int32)
+    w = np.zeros((T, K), dtype=np.float32)
+    gs = E // spec.n_group
+    for t in range(T):
+        if spec.score_fn == SCORE_SIGMOID:
+            s = (1.0 / (1.0 + np.exp(-z[t].astype(np.float64)))).astype(np.float32)
+            c = s + bias.astype(np.float32) if bias is not None else s.copy()
+        else:
+            s = None
+            c = z[t].copy()
+        c = c.astype(np.float32)
+        masked = c.astype(np.float64)
+        if spec.n_group > 1:
+            gscore = np.zeros(spec.n_group, dtype=np.float32)
+            for g in range(spec.n_group):
+                grp = np.sort(c[g * gs:(g + 1) * gs])[::-1]
+                gscore[g] = np.float32(grp[0]) + np.float32(grp[1])
+            keep = _argsort_desc_stable(gscore)[:spec.topk_group]
+            allowed = np.zeros(E, dtype=bool)
+            for g in keep:
+                allowed[g * gs:(g + 1) * gs] = True
+            masked = np.where(allowed, masked, -np.inf)
+        sel = _argsort_desc_stable(masked)[:K]
+        ids[t] = sel
+        if spec.score_fn == SCORE_SIGMOID:
+            sv = s[sel].astype(np.float64)
+            w[t] = (sv / (sv.sum() + 1e-20) * spec.routed_scale).astype(np.float32)
+        else:
+            zv = z[t][sel].astype(np.float64)
+            ex = np.exp(zv - zv.max())
+            w[t] = (ex / ex.sum() * spec.routed_scale).astype(np.float32)
+    return ids, w
+
+
+# --------------------------------------------------------------------------------------
+# Permutation by expert
+# --------------------------------------------------------------------------------------
+
+def permute(topk_ids: np.ndarray, spec: LayerSpec):
+    """Stable counting sort of the flat (token, slot) index f = t*K + k by expert id.
+
+    Returns (expert_offsets int32 [E+1 (+1 if shared)], perm int32 [T*K], inv_perm int32 [T*K]):
+      rows expert_offsets[e] .. expert_offsets[e+1]-1 of the sorted order belong to expert e,
+      perm[r] = f of sorted row r, inv_perm[f] = r.  Within an expert rows keep increasing f
+      (hence increasing token).  With a shared expert one more group follows the routed ones:
+      rows T*K + t for t = 0..T-1, so expert_offsets[E+1] = T*K + T.
+    """
+    T, K = topk_ids.shape
+    flat = topk_ids.reshape(-1)
+    counts = np.zeros(spec.E, dtype=np.int64)
+    for e in flat:
+        counts[e] += 1
+    n_off = spec.E + 1 + (1 if spec.has_shared else 0)
+    offsets = np.zeros(n_off, dtype=np.int32)
+    for e in range(spec.E):
+        offsets[e + 1] = offsets[e] + counts[e]
+    if spec.has_shared:
+        offsets[spec.E + 1] = T * K + T
+    cursor = offsets[:spec.E].astype(np.int64).copy()
+    perm = np.zeros(T * K, dtype=np.int32)
+    inv = np.zeros(T * K, dtype=np.int32)
+    for f in range(T * K):
+        e = flat[f]
+        r = cursor[e]
+        cursor[e] += 1
+        perm[r] = f
+        inv[f] = r
+    return offsets, perm, inv
+
+
+# --------------------------------------------------------------------------------------
+# Expert MLP and the layer
+# --------------------------------------------------------------------------------------
+
+@dataclass
+class ExpertNumpy:
+    """One expert's weights, logical layouts: w13 [2I,H] (gate rows then up rows), w2 [H,I].
+    FP8: uint8 codes + fp32 scales per 128x128 block.  bf16: float arrays holding bf16 values."""
+    w13: np.ndarray
+    w2: np.ndarray
+    s13: Optional[np.ndarray] = None
+    s2: Optional[np.ndarray] = None
+
+    def dense(self) -> Tuple[np.ndarray, np.ndarray]:
+        if self.s13 is None:
+            return self.w13.astype(np.float64), self.w2.astype(np.float64)
+        return dequant_blocks(self.w13, self.s13), dequant_blocks(self.w2, self.s2)
+
+
+def silu(g: np.ndarray) -> np.ndarray:
+    return g / (1.0 + np.exp(-g))
+
+
+def expert_mlp(x_rows: np.ndarray, expert: ExpertNumpy, spec: LayerSpec) -> np.ndarray:
+    """o = W_down ( QDQ( silu(W_gate x~) * (W_up x~) ) ),  x~ = QDQ(x), rows of x_rows at once.
+
+    QDQ is the per-token, per-128 e4m3 activation quantisation and exists only for FP8
+    weights (FP8 matrix cores need an FP8 activation operand, so the quantisation is part of
+    the function both sides compute); for bf16 weights it is the identity.  fp64 everywhere else.
+    """
+    I = spec.I
+    w13, w2 = expert.dense()
+    xr = np.asarray(x_rows, dtype=np.float64)
+    if spec.w_dtype == W_FP8:
+        xr = qdq_act(xr)[0]
+    gu = xr @ w13.T
+    h = silu(gu[:, :I]) * gu[:, I:]
+    if spec.w_dtype == W_FP8:
+        h = qdq_act(h)[0]
+    return h @ w2.T
+
+
+def moe_forward(x: np.ndarray, logits: np.ndarray, bias: Optional[np.ndarray],
+                experts: Sequence[Optional[ExpertNumpy]], spec: LayerSpec,
+                tokens: Optional[Sequence[int]] = None) -> np.ndarray:
+    """y_t = sum_k w_{t,k} * MLP_{e_{t,k}}(x_t)  (+ MLP_shared(x_t), weight 1, not scaled).
+
+    experts[e] for e < E are routed experts, experts[E] the shared one.  Works expert by
+    expert over the permuted rows (one dequantised expert in memory at a time).  `tokens`
+    restricts the output to a subset of tokens (experts none of them selects may be None).
+    Returns fp64 [len(tokens) or T, H].
+    """
+    T = x.shape[0]
+    ids, w = route(logits, bias, spec)
+    tok = np.arange(T) if tokens is None else np.asarray(list(tokens), dtype=np.int64)
+    pos = {int(t): i for i, t in enumerate(tok)}
+    y = np.zeros((len(tok), spec.H), dtype=np.float64)
+    offsets, perm, _ = permute(ids, spec)
+    xf = np.asarray(x, dtype=np.float64)
+    for e in range(spec.E):
+        rows = perm[offsets[e]:offsets[e + 1]]
+        rows = [f for f in rows if (f // spec.K) in pos]
+        if not rows:
+            continue
+        ts = np.array([f // spec.K for f in rows])
+        ks = np.array([f % spec.K for f in rows])
+        o = expert_mlp(xf[ts], experts[e], spec)
+        for i in range(len(rows)):
+            y[pos[int(ts[i])]] += float(w[ts[i], ks[i]]) * o[i]
+    if spec.has_shared:
+        o = expert_mlp(xf[tok], experts[spec.E], spec)
+        y += o
+    return y
+
+
+def moe_forward_bruteforce(x, logits, bias, experts, spec: LayerSpec) -> np.ndarray:
+    """The same function written token by token with no permutation at all: for each token,
+    sort its scores, loop over the chosen experts, add.  Used to pin moe_forward/permute."""
+    T = x.shape[0]
+    ids, w = route(logits, bias, spec)
+    y = np.zeros((T, spec.H), dtype=np.float64)
+    dense = [ex.dense() if ex is not None else None for ex in experts]
+    for t in range(T):
+        xt = np.asarray(x[t], dtype=np.float64)[None, :]
+        if spec.w_dtype == W_FP8:
+            xt = qdq_act(xt)[0]
+        chosen = [(int(ids[t, k]), float(w[t, k])) for k in range(spec.K)]
+        if spec.has_shared:
+            chosen.append((spec.E, 1.0))
+        for e, wk in chosen:
+            w13, w2 = dense[e]
+            g = w13[:spec.I] @ xt[0]
+            u = w13[spec.I:] @ xt[0]
+            h = (g / (1.0 + np.exp(-g)) * u)[None, :]
+            if spec.w_dtype == W_FP8:
+                h = qdq_act(h)[0]
+            y[t] += wk * (w2 @ h[0])
+    return y
+
+
+def error_metrics(y: np.ndarray, ref: np.ndarray) -> Tuple[float, float]:
+    """(max |y-ref| / max |ref|, ||y-ref||_2 / ||ref||_2): the parity metric and an L2 companion."""
+    y = np.asarray(y, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    d = np.abs(y - ref)
+    return float(d.max() / np.abs(ref).max()), float(np.linalg.norm(y - ref) / np.linalg.norm(ref))
