@@ -1,0 +1,214 @@
+/*
+ * dwdp.h -- C ABI of the MI355X (gfx950) DWDP MoE-layer hot path.
+ *
+ * One rank of Distributed Weight Data Parallelism (paper Section 2, "Methodology
+ * Overview"): the rank keeps a subset of each MoE layer's experts resident, pulls the
+ * rest from peers into a double-buffered staging area one layer ahead, and runs the MoE
+ * block as soon as the layer's experts have arrived.  The grouped GEMM reads every
+ * expert through a pointer table, so resident and staged weights are consumed in place
+ * with no merge copy (paper Section 4.2, "Eliminating Split-Weight Merge Overhead").
+ *
+ * General conventions
+ *   - Every data pointer is DEVICE memory owned by the caller unless marked HOST.  The
+ *     library never frees caller memory; it allocates its own workspace in dwdp_create.
+ *   - Calls enqueue work on the context's compute stream (or its private copy stream for
+ *     dwdp_prefetch_layer) and return without waiting.  Buffers must stay valid until
+ *     the stream has passed the call.
+ *   - Errors are return codes; argument errors are detected on the host before anything
+ *     is enqueued.  dwdp_last_error() gives a message for the last failure on a context.
+ *   - Not thread-safe per context; use one context per host thread.
+ *   - Row-major everywhere.  "bf16" is the upper half of an IEEE fp32.  "fp8" is OCP
+ *     e4m3 (finite-only, max 448).
+ */
+#ifndef DWDP_H
+#define DWDP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dwdp_ctx dwdp_ctx;
+
+typedef enum {
+  DWDP_OK = 0,
+  DWDP_EINVAL = 1, /* null pointer, negative size, bad enum                          */
+  DWDP_ESHAPE = 2, /* shape the kernels do not support (see dwdp_create)             */
+  DWDP_ENOMEM = 3, /* workspace allocation failed                                    */
+  DWDP_EHIP = 4,   /* a HIP runtime call failed; message holds the HIP error string  */
+  DWDP_ESTATE = 5  /* call order violates the double-buffer protocol                 */
+} dwdp_status;
+
+enum { DWDP_SCORE_SOFTMAX = 0, DWDP_SCORE_SIGMOID = 1 };
+enum { DWDP_W_BF16 = 0, DWDP_W_FP8 = 1 };
+
+/* Shape and routing parameters of one MoE layer; all layers of a context share them. */
+typedef struct {
+  int32_t T_max;        /* largest token count of any call                                  */
+  int32_t H;            /* hidden size                                                       */
+  int32_t I;            /* expert intermediate size                                          */
+  int32_t E;            /* routed experts                                                    */
+  int32_t K;            /* experts per token                                                 */
+  int32_t n_group;      /* expert groups for group-limited routing (1 = none)                */
+  int32_t topk_group;   /* groups kept per token                                             */
+  int32_t has_shared;   /* 1: slot E of the table is an always-on shared expert              */
+  int32_t score_fn;     /* DWDP_SCORE_*                                                      */
+  float routed_scale;   /* routing weights of a token sum to this                            */
+  int32_t w_dtype;      /* DWDP_W_*                                                          */
+  int32_t n_layers;     /* layers that will be addressed by dwdp_moe_forward/prefetch (>=1)  */
+} dwdp_config;
+
+/*
+ * One row of the expert-pointer table (the "TensorList" of paper Section 4.2): where one
+ * expert's weights are.  Entries may point into resident memory or into a staging
+ * buffer; the kernels do not care.  Slot e < E is routed expert e, slot E the shared one.
+ *   w13  [2I, H]  rows 0..I-1 gate projection, rows I..2I-1 up projection
+ *   w2   [H, I]   down projection
+ *   FP8:  1 byte/element; s13 fp32 [2I/128, H/128], s2 fp32 [H/128, I/128]: one scale per
+ *         128x128 block, weight = decode(byte) * scale.  Pointers 16-byte aligned.
+ *   bf16: 2 bytes/element; s13 = s2 = NULL.
+ */
+typedef struct {
+  const void* w13;
+  const float* s13;
+  const void* w2;
+  const float* s2;
+} dwdp_expert_ptrs;
+
+/*
+ * Create a context bound to `compute_stream` (a hipStream_t; NULL = the default stream)
+ * on the current device.  Allocates the workspace for T_max tokens and a private copy
+ * stream at default priority.
+ * Supported shapes: H, I multiples of 128; 1 <= K <= E <= 1024; K <= 32; E % n_group == 0;
+ * at least 2 experts per group when n_group > 1; K <= topk_group * E / n_group.
+ * DWDP_ESHAPE otherwise.
+ */
+dwdp_status dwdp_create(const dwdp_config* cfg, void* compute_stream, dwdp_ctx** out);
+void dwdp_destroy(dwdp_ctx* ctx);
+/* Message of the last failure on ctx (or of the last failed dwdp_create if ctx is NULL). */
+const char* dwdp_last_error(const dwdp_ctx* ctx);
+
+/*
+ * Router top-k (the MoE arithmetic is DeepSeek-V3's, which the paper's Section 5.1 names
+ * as the evaluated model).  logits fp32 [T,E]; bias fp32 [E] or NULL.
+ *   sigmoid: s = fp32(1/(1+exp(-fp64(z)))); selection score c = s + bias (fp32 add);
+ *            group score = sum of the two largest c of the group; keep topk_group groups,
+ *            then the K largest c among them; w_k = s_k / (sum_j s_j + 1e-20) * routed_scale.
+ *   softmax: selection on the raw logits (bias ignored), w = softmax over the K selected
+ *            logits * routed_scale.
+ * Ties go to the lower index; topk_ids [T,K] int32 are ordered by descending selection
+ * score; topk_w [T,K] fp32.  T = 0 is a no-op.
+ */
+dwdp_status dwdp_route(dwdp_ctx* ctx, const float* logits, const float* bias, int32_t T,
+                       int32_t* topk_ids, float* topk_w);
+
+/*
+ * Permutation by expert: stable counting sort of f = t*K + k by topk_ids[f].
+ *   expert_offsets int32 [E+1 (+1 if has_shared)]  exclusive prefix sums; with a shared
+ *                  expert the last entry is T*K + T (its rows are T*K + t)
+ *   perm     int32 [T*K]  perm[r] = f of sorted row r
+ *   inv_perm int32 [T*K]  inv_perm[f] = r
+ * Every topk_ids value must be in [0,E) (values outside are ignored by the histogram and
+ * leave their perm rows unwritten).  T = 0 writes all-zero offsets.
+ */
+dwdp_status dwdp_permute(dwdp_ctx* ctx, const int32_t* topk_ids, int32_t T,
+                         int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm);
+
+/*
+ * One MoE layer forward: route -> permute -> (FP8: quantise x per token per 128) ->
+ * grouped GEMM gate/up + SwiGLU (FP8: quantise h per token per 128) -> grouped GEMM down
+ * -> y[t] = sum_k w[t,k] * out[t,k] (+ shared expert, weight 1).
+ *   x bf16 [T,H]; logits fp32 [T,E]; bias fp32 [E] or NULL; table [E (+1)] rows of
+ *   dwdp_expert_ptrs in DEVICE memory; y bf16 [T,H] out.
+ * If dwdp_prefetch_layer(layer) was issued and not yet consumed, the compute stream first
+ * waits for its copies (paper Section 2: a layer waits until all remote experts have
+ * arrived); when the layer is done its staging buffer (layer % 2) is released for the
+ * next prefetch.  0 <= layer < n_layers.  Experts with no tokens are never read.
+ */
+dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void* x, const float* logits,
+                             const float* bias, int32_t T, const dwdp_expert_ptrs* table, void* y);
+
+/*
+ * Prefetch the non-resident experts of `layer` into staging buffer layer % 2 on the
+ * context's copy stream, as the batched copy plan in round-robin slice order of paper
+ * Section 4.3.2 (Listing 1): for each parameter p, for each slice offset, for each peer in
+ * the given order, one asynchronous device copy of min(slice_bytes, bytes[p] - offset).
+ *   src, dst  HOST arrays [n_peers * n_params] of device pointers, index peer*n_params + p:
+ *             the peer's region of parameter p and its place in the staging buffer
+ *   bytes     HOST array [n_params]: bytes pulled of parameter p from each peer
+ * The copies start only after the previous reader of that staging buffer has finished
+ * (double buffering, paper Section 2).  DWDP_ESTATE if the buffer still holds a prefetched
+ * layer that no dwdp_moe_forward has consumed.  slice_bytes = 0 means unsliced.
+ */
+dwdp_status dwdp_prefetch_layer(dwdp_ctx* ctx, int32_t layer, const void* const* src, void* const* dst,
+                                const size_t* bytes, int32_t n_peers, int32_t n_params, size_t slice_bytes);
+
+/*
+ * Host-only: the copy plan dwdp_prefetch_layer would issue, written to HOST arrays of
+ * capacity `cap` entries (may be NULL with cap = 0 to query the length).  *n_out receives
+ * the plan length.  Same argument meaning as dwdp_prefetch_layer.  Touches no GPU.
+ */
+dwdp_status dwdp_build_copy_plan(const void* const* src, void* const* dst, const size_t* bytes,
+                                 int32_t n_peers, int32_t n_params, size_t slice_bytes,
+                                 void** plan_dst, const void** plan_src, size_t* plan_bytes,
+                                 size_t cap, size_t* n_out);
+
+/*
+ * Naive split-weight baseline of paper Section 4.2: merge the experts named by `table`
+ * (DEVICE, n_slots rows) into contiguous caller buffers with device-to-device copies on
+ * the compute stream and write the table of the merged copy to merged_table (DEVICE).
+ * w13_out/w2_out/s13_out/s2_out hold n_slots experts back to back.
+ * table_host is the HOST copy of `table` (the library cannot read device memory on the host).
+ */
+dwdp_status dwdp_merge_experts(dwdp_ctx* ctx, const dwdp_expert_ptrs* table_host, int32_t n_slots,
+                               void* w13_out, float* s13_out, void* w2_out, float* s2_out,
+                               dwdp_expert_ptrs* merged_table_host);
+
+/*
+ * Per-stage timing with HIP events on the compute stream.  While enabled, every
+ * dwdp_moe_forward records an event before each stage.  dwdp_profile_read synchronises
+ * the stream, adds up the elapsed milliseconds per stage over the calls since the last
+ * read into ms_sum[DWDP_N_STAGES] (HOST), stores the number of calls in *n_calls and
+ * resets.  At most DWDP_PROFILE_MAX_CALLS calls are kept between reads.
+ */
+enum {
+  DWDP_STAGE_ROUTE = 0,
+  DWDP_STAGE_PERMUTE = 1,
+  DWDP_STAGE_QUANT = 2,
+  DWDP_STAGE_GEMM1 = 3,
+  DWDP_STAGE_GEMM2 = 4,
+  DWDP_STAGE_COMBINE = 5,
+  DWDP_N_STAGES = 6
+};
+enum { DWDP_PROFILE_MAX_CALLS = 512 };
+dwdp_status dwdp_profile_enable(dwdp_ctx* ctx, int32_t on);
+dwdp_status dwdp_profile_read(dwdp_ctx* ctx, float* ms_sum, int32_t* n_calls);
+
+/*
+ * Device pointers of the context's workspace for inspection by tests (valid until
+ * dwdp_destroy; contents are those of the last dwdp_moe_forward once the stream is idle).
+ */
+enum {
+  DWDP_WS_TOPK_IDS = 0, /* int32 [T,K]                      */
+  DWDP_WS_TOPK_W = 1,   /* fp32  [T,K]                      */
+  DWDP_WS_OFFSETS = 2,  /* int32 [E+1(+1)]                  */
+  DWDP_WS_PERM = 3,     /* int32 [T*K]                      */
+  DWDP_WS_INV_PERM = 4, /* int32 [T*K]                      */
+  DWDP_WS_XQ = 5,       /* fp8 [T,H]          (FP8 only)    */
+  DWDP_WS_XS = 6,       /* fp32 [T,H/128]     (FP8 only)    */
+  DWDP_WS_HQ = 7,       /* fp8 (FP8) or fp32 (bf16) [rows,I] */
+  DWDP_WS_HS = 8,       /* fp32 [rows,I/128]  (FP8 only)    */
+  DWDP_WS_YP = 9,       /* bf16 (FP8) or fp32 (bf16) [rows,H] */
+  DWDP_N_WS = 10
+};
+void* dwdp_workspace_ptr(dwdp_ctx* ctx, int32_t which);
+
+/* The copy stream (hipStream_t) used by dwdp_prefetch_layer, for tracing and tests. */
+void* dwdp_copy_stream(dwdp_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DWDP_H */

@@ -1,0 +1,367 @@
+// C-ABI entry points of libdwdp: argument checking, workspace, stream/event choreography
+// of the layer-ahead prefetch pipeline.  All arithmetic lives in the kernels.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "dwdp_kernels.h"
+
+using namespace dwdp;
+
+struct dwdp_ctx {
+  dwdp_config cfg{};
+  int device = 0;
+  hipStream_t compute = nullptr;
+  hipStream_t copy = nullptr;
+  int n_slots = 0;
+  size_t rows_max = 0;
+  void* ws[DWDP_N_WS] = {};
+  int32_t* chunk_counts = nullptr;
+  // double-buffer protocol
+  std::vector<hipEvent_t> staged_ev;  // per layer: its prefetch copies are complete
+  hipEvent_t done_ev[2] = {nullptr, nullptr};  // per staging buffer: its last reader finished
+  bool done_valid[2] = {false, false};
+  int pending_layer[2] = {-1, -1};  // layer prefetched into the buffer and not yet consumed
+  // profiling
+  bool prof = false;
+  std::vector<hipEvent_t> prof_ev;
+  int prof_calls = 0;
+  std::string err;
+};
+
+static thread_local std::string g_create_err;
+
+static dwdp_status fail(dwdp_ctx* ctx, dwdp_status st, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (ctx)
+    ctx->err = buf;
+  else
+    g_create_err = buf;
+  return st;
+}
+
+#define HIP_TRY(ctx, call)                                                                        \
+  do {                                                                                            \
+    hipError_t e_ = (call);                                                                       \
+    if (e_ != hipSuccess) return fail(ctx, DWDP_EHIP, "%s: %s", #call, hipGetErrorString(e_));    \
+  } while (0)
+
+static dwdp_status check_config(const dwdp_config* c) {
+  if (!c) return fail(nullptr, DWDP_EINVAL, "cfg is NULL");
+  if (c->T_max < 0 || c->H <= 0 || c->I <= 0 || c->E <= 0 || c->K <= 0 || c->n_layers < 1)
+    return fail(nullptr, DWDP_EINVAL, "non-positive size in cfg");
+  if (c->score_fn != DWDP_SCORE_SOFTMAX && c->score_fn != DWDP_SCORE_SIGMOID)
+    return fail(nullptr, DWDP_EINVAL, "score_fn must be DWDP_SCORE_SOFTMAX or DWDP_SCORE_SIGMOID");
+  if (c->w_dtype != DWDP_W_BF16 && c->w_dtype != DWDP_W_FP8)
+    return fail(nullptr, DWDP_EINVAL, "w_dtype must be DWDP_W_BF16 or DWDP_W_FP8");
+  if (c->has_shared != 0 && c->has_shared != 1) return fail(nullptr, DWDP_EINVAL, "has_shared must be 0 or 1");
+  if (c->H % 128 || c->I % 128) return fail(nullptr, DWDP_ESHAPE, "H and I must be multiples of 128");
+  if (c->E > 1024 || c->K > c->E || c->K > 32) return fail(nullptr, DWDP_ESHAPE, "need K <= E <= 1024 and K <= 32");
+  if (c->n_group < 1 || c->n_group > 64 || c->E % c->n_group)
+    return fail(nullptr, DWDP_ESHAPE, "n_group must divide E and be in [1,64]");
+  if (c->topk_group < 1 || c->topk_group > c->n_group)
+    return fail(nullptr, DWDP_ESHAPE, "topk_group must be in [1,n_group]");
+  if (c->n_group > 1 && c->E / c->n_group < 2)
+    return fail(nullptr, DWDP_ESHAPE, "group-limited routing needs at least 2 experts per group");
+  if ((long)c->K > (long)c->topk_group * (c->E / c->n_group))
+    return fail(nullptr, DWDP_ESHAPE, "K exceeds the experts of the kept groups");
+  if ((long)c->T_max * c->K > (1L << 30)) return fail(nullptr, DWDP_ESHAPE, "T_max * K too large");
+  return DWDP_OK;
+}
+
+extern "C" dwdp_status dwdp_create(const dwdp_config* cfg, void* compute_stream, dwdp_ctx** out) {
+  if (!out) return fail(nullptr, DWDP_EINVAL, "out is NULL");
+  *out = nullptr;
+  dwdp_status st = check_config(cfg);
+  if (st != DWDP_OK) return st;
+  dwdp_ctx* c = new (std::nothrow) dwdp_ctx();
+  if (!c) return fail(nullptr, DWDP_ENOMEM, "host allocation failed");
+  c->cfg = *cfg;
+  c->compute = (hipStream_t)compute_stream;
+  c->n_slots = cfg->E + cfg->has_shared;
+  const size_t T = (size_t)(cfg->T_max > 0 ? cfg->T_max : 1);
+  const size_t K = cfg->K, H = cfg->H, I = cfg->I, E = cfg->E;
+  c->rows_max = T * K + (cfg->has_shared ? T : 0);
+  const bool fp8 = cfg->w_dtype == DWDP_W_FP8;
+  size_t bytes[DWDP_N_WS];
+  bytes[DWDP_WS_TOPK_IDS] = T * K * 4;
+  bytes[DWDP_WS_TOPK_W] = T * K * 4;
+  bytes[DWDP_WS_OFFSETS] = (E + 2) * 4;
+  bytes[DWDP_WS_PERM] = T * K * 4;
+  bytes[DWDP_WS_INV_PERM] = T * K * 4;
+  bytes[DWDP_WS_XQ] = fp8 ? T * H : 0;
+  bytes[DWDP_WS_XS] = fp8 ? T * (H / 128) * 4 : 0;
+  bytes[DWDP_WS_HQ] = c->rows_max * I * (fp8 ? 1 : 4);
+  bytes[DWDP_WS_HS] = fp8 ? c->rows_max * (I / 128) * 4 : 0;
+  bytes[DWDP_WS_YP] = c->rows_max * H * (fp8 ? 2 : 4);
+  hipError_t e = hipGetDevice(&c->device);
+  for (int i = 0; i < DWDP_N_WS && e == hipSuccess; i++)
+    if (bytes[i]) e = hipMalloc(&c->ws[i], bytes[i]);
+  const int chunk = permute_chunk_tokens(cfg->E);
+  const size_t n_chunks = (T + chunk - 1) / chunk;
+  if (e == hipSuccess) e = hipMalloc((void**)&c->chunk_counts, n_chunks * E * 4);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->copy, hipStreamNonBlocking);
+  c->staged_ev.assign(cfg->n_layers, nullptr);
+  for (int l = 0; l < cfg->n_layers && e == hipSuccess; l++)
+    e = hipEventCreateWithFlags(&c->staged_ev[l], hipEventDisableTiming);
+  for (int b = 0; b < 2 && e == hipSuccess; b++) e = hipEventCreateWithFlags(&c->done_ev[b], hipEventDisableTiming);
+  if (e != hipSuccess) {
+    dwdp_status s = fail(nullptr, e == hipErrorOutOfMemory ? DWDP_ENOMEM : DWDP_EHIP, "dwdp_create: %s",
+                         hipGetErrorString(e));
+    dwdp_destroy(c);
+    return s;
+  }
+  *out = c;
+  return DWDP_OK;
+}
+
+extern "C" void dwdp_destroy(dwdp_ctx* c) {
+  if (!c) return;
+  if (c->compute || c->copy) (void)hipDeviceSynchronize();
+  for (void* p : c->ws)
+    if (p) (void)hipFree(p);
+  if (c->chunk_counts) (void)hipFree(c->chunk_counts);
+  for (hipEvent_t ev : c->staged_ev)
+    if (ev) (void)hipEventDestroy(ev);
+  for (hipEvent_t ev : c->done_ev)
+    if (ev) (void)hipEventDestroy(ev);
+  for (hipEvent_t ev : c->prof_ev)
+    if (ev) (void)hipEventDestroy(ev);
+  if (c->copy) (void)hipStreamDestroy(c->copy);
+  delete c;
+}
+
+extern "C" const char* dwdp_last_error(const dwdp_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_err.c_str(); }
+
+static RouteParams route_params(const dwdp_config& c) {
+  return RouteParams{c.E, c.K, c.n_group, c.topk_group, c.score_fn, c.routed_scale};
+}
+
+static dwdp_status check_T(dwdp_ctx* ctx, int32_t T) {
+  if (T < 0) return fail(ctx, DWDP_EINVAL, "T is negative");
+  if (T > ctx->cfg.T_max) return fail(ctx, DWDP_ESHAPE, "T = %d exceeds T_max = %d", T, ctx->cfg.T_max);
+  return DWDP_OK;
+}
+
+extern "C" dwdp_status dwdp_route(dwdp_ctx* ctx, const float* logits, const float* bias, int32_t T, int32_t* topk_ids,
+                                  float* topk_w) {
+  if (!ctx) return DWDP_EINVAL;
+  dwdp_status st = check_T(ctx, T);
+  if (st != DWDP_OK) return st;
+  if (T == 0) return DWDP_OK;
+  if (!logits || !topk_ids || !topk_w) return fail(ctx, DWDP_EINVAL, "dwdp_route: NULL pointer");
+  launch_route(logits, ctx->cfg.score_fn == DWDP_SCORE_SIGMOID ? bias : nullptr, T, route_params(ctx->cfg), topk_ids,
+               topk_w, ctx->compute);
+  HIP_TRY(ctx, hipGetLastError());
+  return DWDP_OK;
+}
+
+extern "C" dwdp_status dwdp_permute(dwdp_ctx* ctx, const int32_t* topk_ids, int32_t T, int32_t* expert_offsets,
+                                    int32_t* perm, int32_t* inv_perm) {
+  if (!ctx) return DWDP_EINVAL;
+  dwdp_status st = check_T(ctx, T);
+  if (st != DWDP_OK) return st;
+  if (!expert_offsets) return fail(ctx, DWDP_EINVAL, "dwdp_permute: expert_offsets is NULL");
+  if (T > 0 && (!topk_ids || !perm || !inv_perm)) return fail(ctx, DWDP_EINVAL, "dwdp_permute: NULL pointer");
+  launch_permute(topk_ids, T, ctx->cfg.E, ctx->cfg.K, ctx->cfg.has_shared, ctx->chunk_counts, expert_offsets, perm,
+                 inv_perm, ctx->compute);
+  HIP_TRY(ctx, hipGetLastError());
+  return DWDP_OK;
+}
+
+static inline hipEvent_t prof_event(dwdp_ctx* ctx, int stage) {
+  return ctx->prof_ev[(size_t)ctx->prof_calls * (DWDP_N_STAGES + 1) + stage];
+}
+
+extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void* x, const float* logits,
+                                        const float* bias, int32_t T, const dwdp_expert_ptrs* table, void* y) {
+  if (!ctx) return DWDP_EINVAL;
+  dwdp_status st = check_T(ctx, T);
+  if (st != DWDP_OK) return st;
+  const dwdp_config& c = ctx->cfg;
+  if (layer < 0 || layer >= c.n_layers) return fail(ctx, DWDP_EINVAL, "layer %d outside [0,%d)", layer, c.n_layers);
+  if (T > 0 && (!x || !logits || !table || !y)) return fail(ctx, DWDP_EINVAL, "dwdp_moe_forward: NULL pointer");
+  hipStream_t s = ctx->compute;
+  const int b = layer & 1;
+  const bool consume = ctx->pending_layer[b] == layer;
+  if (T == 0) {
+    // nothing to compute, but the staging buffer is still released in stream order
+    if (consume) HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->staged_ev[layer], 0));
+    HIP_TRY(ctx, hipEventRecord(ctx->done_ev[b], s));
+    ctx->done_valid[b] = true;
+    if (consume) ctx->pending_layer[b] = -1;
+    return DWDP_OK;
+  }
+  const bool prof = ctx->prof && ctx->prof_calls < DWDP_PROFILE_MAX_CALLS;
+  int32_t* ids = (int32_t*)ctx->ws[DWDP_WS_TOPK_IDS];
+  float* tw = (float*)ctx->ws[DWDP_WS_TOPK_W];
+  int32_t* off = (int32_t*)ctx->ws[DWDP_WS_OFFSETS];
+  int32_t* perm = (int32_t*)ctx->ws[DWDP_WS_PERM];
+  int32_t* inv = (int32_t*)ctx->ws[DWDP_WS_INV_PERM];
+
+  if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_ROUTE), s));
+  launch_route(logits, c.score_fn == DWDP_SCORE_SIGMOID ? bias : nullptr, T, route_params(c), ids, tw, s);
+  if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_PERMUTE), s));
+  launch_permute(ids, T, c.E, c.K, c.has_shared, ctx->chunk_counts, off, perm, inv, s);
+  if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_QUANT), s));
+  GemmArgs ga{table, off, perm, ctx->n_slots, c.E, T, c.H, c.I, c.K};
+  const bool fp8 = c.w_dtype == DWDP_W_FP8;
+  if (fp8) launch_quant_act(x, T, c.H, (uint8_t*)ctx->ws[DWDP_WS_XQ], (float*)ctx->ws[DWDP_WS_XS], s);
+  // Only the grouped GEMMs read expert weights: the wait for the staged experts goes here.
+  if (consume) HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->staged_ev[layer], 0));
+  if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM1), s));
+  if (fp8)
+    launch_gemm1_fp8(ga, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
+                     (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], s);
+  else
+    launch_gemm1_bf16(ga, x, ctx->ws[DWDP_WS_HQ], s);
+  if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM2), s));
+  if (fp8)
+    launch_gemm2_fp8(ga, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS], ctx->ws[DWDP_WS_YP],
+                     s);
+  else
+    launch_gemm2_bf16(ga, ctx->ws[DWDP_WS_HQ], ctx->ws[DWDP_WS_YP], s);
+  // The layer's weights have been read once GEMM-2 is done: release the staging buffer here.
+  HIP_TRY(ctx, hipEventRecord(ctx->done_ev[b], s));
+  ctx->done_valid[b] = true;
+  if (consume) ctx->pending_layer[b] = -1;
+  if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_COMBINE), s));
+  launch_combine(ctx->ws[DWDP_WS_YP], !fp8, inv, tw, T, c.H, c.K, c.has_shared, y, s);
+  if (prof) {
+    HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_N_STAGES), s));
+    ctx->prof_calls++;
+  }
+  HIP_TRY(ctx, hipGetLastError());
+  return DWDP_OK;
+}
+
+extern "C" dwdp_status dwdp_build_copy_plan(const void* const* src, void* const* dst, const size_t* bytes,
+                                            int32_t n_peers, int32_t n_params, size_t slice_bytes, void** plan_dst,
+                                            const void** plan_src, size_t* plan_bytes, size_t cap, size_t* n_out) {
+  if (!src || !dst || !bytes || !n_out || n_peers < 0 || n_params < 0) return DWDP_EINVAL;
+  if (cap > 0 && (!plan_dst || !plan_src || !plan_bytes)) return DWDP_EINVAL;
+  size_t n = 0;
+  for (int p = 0; p < n_params; p++) {
+    const size_t M = bytes[p];
+    const size_t s = slice_bytes ? slice_bytes : (M ? M : 1);
+    for (size_t offset = 0; offset < M; offset += s) {
+      const size_t chunk = M - offset < s ? M - offset : s;
+      for (int peer = 0; peer < n_peers; peer++) {
+        const size_t idx = (size_t)peer * n_params + p;
+        if (n < cap) {
+          plan_dst[n] = (char*)dst[idx] + offset;
+          plan_src[n] = (const char*)src[idx] + offset;
+          plan_bytes[n] = chunk;
+        }
+        n++;
+      }
+    }
+  }
+  *n_out = n;
+  return DWDP_OK;
+}
+
+extern "C" dwdp_status dwdp_prefetch_layer(dwdp_ctx* ctx, int32_t layer, const void* const* src, void* const* dst,
+                                           const size_t* bytes, int32_t n_peers, int32_t n_params,
+                                           size_t slice_bytes) {
+  if (!ctx) return DWDP_EINVAL;
+  if (layer < 0 || layer >= ctx->cfg.n_layers)
+    return fail(ctx, DWDP_EINVAL, "layer %d outside [0,%d)", layer, ctx->cfg.n_layers);
+  if (!src || !dst || !bytes || n_peers < 0 || n_params < 0)
+    return fail(ctx, DWDP_EINVAL, "dwdp_prefetch_layer: NULL pointer or negative count");
+  for (int i = 0; i < n_peers * n_params; i++)
+    if (bytes[i % n_params] && (!src[i] || !dst[i])) return fail(ctx, DWDP_EINVAL, "NULL region pointer at %d", i);
+  const int b = layer & 1;
+  if (ctx->pending_layer[b] != -1)
+    return fail(ctx, DWDP_ESTATE, "staging buffer %d still holds layer %d, which no dwdp_moe_forward has consumed", b,
+                ctx->pending_layer[b]);
+  size_t n = 0;
+  dwdp_status st = dwdp_build_copy_plan(src, dst, bytes, n_peers, n_params, slice_bytes, nullptr, nullptr, nullptr, 0,
+                                        &n);
+  if (st != DWDP_OK) return fail(ctx, st, "copy plan");
+  std::vector<void*> pd(n);
+  std::vector<const void*> ps(n);
+  std::vector<size_t> pb(n);
+  dwdp_build_copy_plan(src, dst, bytes, n_peers, n_params, slice_bytes, pd.data(), ps.data(), pb.data(), n, &n);
+  // double buffering: the buffer is free once its previous reader has finished
+  if (ctx->done_valid[b]) HIP_TRY(ctx, hipStreamWaitEvent(ctx->copy, ctx->done_ev[b], 0));
+  for (size_t i = 0; i < n; i++)
+    HIP_TRY(ctx, hipMemcpyAsync(pd[i], ps[i], pb[i], hipMemcpyDeviceToDevice, ctx->copy));
+  HIP_TRY(ctx, hipEventRecord(ctx->staged_ev[layer], ctx->copy));
+  ctx->pending_layer[b] = layer;
+  return DWDP_OK;
+}
+
+extern "C" dwdp_status dwdp_merge_experts(dwdp_ctx* ctx, const dwdp_expert_ptrs* table_host, int32_t n_slots,
+                                          void* w13_out, float* s13_out, void* w2_out, float* s2_out,
+                                          dwdp_expert_ptrs* merged_table_host) {
+  if (!ctx) return DWDP_EINVAL;
+  if (!table_host || !merged_table_host || !w13_out || !w2_out || n_slots < 0)
+    return fail(ctx, DWDP_EINVAL, "dwdp_merge_experts: NULL pointer");
+  const dwdp_config& c = ctx->cfg;
+  const bool fp8 = c.w_dtype == DWDP_W_FP8;
+  if (fp8 && (!s13_out || !s2_out)) return fail(ctx, DWDP_EINVAL, "dwdp_merge_experts: scale outputs are NULL");
+  const size_t el = fp8 ? 1 : 2;
+  const size_t b13 = (size_t)2 * c.I * c.H * el, b2 = (size_t)c.H * c.I * el;
+  const size_t n13 = (size_t)(2 * c.I / 128) * (c.H / 128), n2 = (size_t)(c.H / 128) * (c.I / 128);
+  for (int e = 0; e < n_slots; e++) {
+    dwdp_expert_ptrs m{};
+    m.w13 = (char*)w13_out + e * b13;
+    m.w2 = (char*)w2_out + e * b2;
+    HIP_TRY(ctx, hipMemcpyAsync((void*)m.w13, table_host[e].w13, b13, hipMemcpyDeviceToDevice, ctx->compute));
+    HIP_TRY(ctx, hipMemcpyAsync((void*)m.w2, table_host[e].w2, b2, hipMemcpyDeviceToDevice, ctx->compute));
+    if (fp8) {
+      m.s13 = s13_out + e * n13;
+      m.s2 = s2_out + e * n2;
+      HIP_TRY(ctx, hipMemcpyAsync((void*)m.s13, table_host[e].s13, n13 * 4, hipMemcpyDeviceToDevice, ctx->compute));
+      HIP_TRY(ctx, hipMemcpyAsync((void*)m.s2, table_host[e].s2, n2 * 4, hipMemcpyDeviceToDevice, ctx->compute));
+    }
+    merged_table_host[e] = m;
+  }
+  return DWDP_OK;
+}
+
+extern "C" dwdp_status dwdp_profile_enable(dwdp_ctx* ctx, int32_t on) {
+  if (!ctx) return DWDP_EINVAL;
+  if (on && ctx->prof_ev.empty()) {
+    ctx->prof_ev.assign((size_t)DWDP_PROFILE_MAX_CALLS * (DWDP_N_STAGES + 1), nullptr);
+    for (auto& ev : ctx->prof_ev) HIP_TRY(ctx, hipEventCreate(&ev));
+  }
+  ctx->prof = on != 0;
+  ctx->prof_calls = 0;
+  return DWDP_OK;
+}
+
+extern "C" dwdp_status dwdp_profile_read(dwdp_ctx* ctx, float* ms_sum, int32_t* n_calls) {
+  if (!ctx) return DWDP_EINVAL;
+  if (!ms_sum || !n_calls) return fail(ctx, DWDP_EINVAL, "dwdp_profile_read: NULL pointer");
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->compute));
+  for (int s = 0; s < DWDP_N_STAGES; s++) ms_sum[s] = 0.f;
+  for (int i = 0; i < ctx->prof_calls; i++) {
+    for (int s = 0; s < DWDP_N_STAGES; s++) {
+      float ms = 0.f;
+      HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->prof_ev[(size_t)i * (DWDP_N_STAGES + 1) + s],
+                                       ctx->prof_ev[(size_t)i * (DWDP_N_STAGES + 1) + s + 1]));
+      ms_sum[s] += ms;
+    }
+  }
+  *n_calls = ctx->prof_calls;
+  ctx->prof_calls = 0;
+  return DWDP_OK;
+}
+
+extern "C" void* dwdp_workspace_ptr(dwdp_ctx* ctx, int32_t which) {
+  if (!ctx || which < 0 || which >= DWDP_N_WS) return nullptr;
+  return ctx->ws[which];
+}
+
+extern "C" void* dwdp_copy_stream(dwdp_ctx* ctx) { return ctx ? (void*)ctx->copy : nullptr; }

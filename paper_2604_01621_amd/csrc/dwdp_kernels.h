@@ -1,0 +1,80 @@
+// Internal launch interface between the C-ABI host code and the gfx950 kernels.
+// Device pointers only; every function enqueues on `stream` and returns.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/dwdp.h"
+
+namespace dwdp {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+constexpr int kWave = 64;
+constexpr int kBlockScale = 128;  // side of a weight scale block = activation quantisation group
+
+struct RouteParams {
+  int E, K, n_group, topk_group, score_fn;
+  float routed_scale;
+};
+
+// Tokens per permutation chunk for E experts (bitmask of E x chunk bits must fit 48 KiB of LDS).
+int permute_chunk_tokens(int E);
+
+void launch_route(const float* logits, const float* bias, int T, const RouteParams& p, int32_t* ids, float* w,
+                  hipStream_t stream);
+
+// chunk_counts: int32 [n_chunks * E] scratch.
+void launch_permute(const int32_t* ids, int T, int E, int K, int has_shared, int32_t* chunk_counts,
+                    int32_t* offsets, int32_t* perm, int32_t* inv_perm, hipStream_t stream);
+
+// x bf16 [T,H] -> xq fp8 [T,H], xs fp32 [T,H/128]
+void launch_quant_act(const void* x, int T, int H, uint8_t* xq, float* xs, hipStream_t stream);
+
+// y[t] = sum_k w[t,k] * yp[inv_perm[t*K+k]] (+ yp[T*K+t]); yp bf16 or fp32 [rows,H]; y bf16 [T,H]
+void launch_combine(const void* yp, bool yp_fp32, const int32_t* inv_perm, const float* topk_w, int T, int H, int K,
+                    int has_shared, void* y, hipStream_t stream);
+
+struct GemmArgs {
+  const dwdp_expert_ptrs* table;  // device, n_slots rows
+  const int32_t* offsets;         // device, n_slots + 1
+  const int32_t* perm;            // device, T*K
+  int n_slots, E, T, H, I, K;
+};
+
+// FP8: h = quant(silu(Xq Wg^T) * (Xq Wu^T)); hq fp8 [rows,I], hs fp32 [rows,I/128]
+void launch_gemm1_fp8(const GemmArgs& a, const uint8_t* xq, const float* xs, uint8_t* hq, float* hs,
+                      hipStream_t stream);
+// FP8: yp = Hq W2^T, bf16 [rows,H]
+void launch_gemm2_fp8(const GemmArgs& a, const uint8_t* hq, const float* hs, void* yp, hipStream_t stream);
+// bf16 weights and activations: h fp32 [rows,I]; yp fp32 [rows,H]
+void launch_gemm1_bf16(const GemmArgs& a, const void* x, void* h, hipStream_t stream);
+void launch_gemm2_bf16(const GemmArgs& a, const void* h, void* yp, hipStream_t stream);
+
+// ---- small device helpers shared by the kernels ----
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// Round-to-nearest-even fp32 -> bf16 (inputs are finite here).
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// Four fp32 -> four e4m3 bytes (hardware RNE conversion; inputs clamped to +-448 first).
+__device__ __forceinline__ uint32_t pack_fp8x4(float a, float b, float c, float d) {
+  a = __builtin_fminf(__builtin_fmaxf(a, -448.f), 448.f);
+  b = __builtin_fminf(__builtin_fmaxf(b, -448.f), 448.f);
+  c = __builtin_fminf(__builtin_fmaxf(c, -448.f), 448.f);
+  d = __builtin_fminf(__builtin_fmaxf(d, -448.f), 448.f);
+  int v = 0;
+  v = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, v, false);
+  v = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, v, true);
+  return (uint32_t)v;
+}
+
+}  // namespace dwdp

@@ -1,0 +1,328 @@
+// Weight-streaming grouped GEMM for gfx950: the small-M (decode-shaped) path.
+//
+// With a handful of tokens per expert the layer is bound by reading each activated
+// expert's weights from HBM exactly once.  The kernels below therefore treat the weights
+// as a stream: a workgroup owns a panel of 128 weight rows of one expert (located through
+// the expert-pointer table, so resident and staged experts look the same), every lane
+// loads its 32-byte slice of a 16x128 MFMA operand straight from global memory into
+// registers (no LDS: nothing is reused between waves), and 2*kU K-blocks of loads are kept
+// in flight per wave while v_mfma_f32_16x16x128_f8f6f4 consumes the previous ones.
+//
+// Operand roles: A = weights (16 rows n x 128 k), B = activations (128 k x 16 tokens), so a
+// lane's 4 accumulators are 4 consecutive n for ONE token (lane & 15).  One MFMA covers
+// exactly one 128-wide K block, i.e. one weight-scale block and one activation-scale
+// group; its fp32 result is multiplied by s_act[token,kb] * s_w[nblock,kb] and added to the
+// running accumulator on the VALU.
+//
+// Experts with more than 16 tokens loop over 16-token tiles and re-stream the panel (served
+// by L2 / Infinity Cache); large-M workloads use the LDS-tiled kernel instead.
+#include "dwdp_kernels.h"
+
+namespace dwdp {
+
+constexpr int kU = 2;             // K blocks per pipeline half
+constexpr int kStreamThreads = 256;
+
+template <int NT>
+struct Frag {
+  v4i w[NT][2];
+  v4i x[2];
+  float sa;
+  float sw[2];
+};
+
+__device__ __forceinline__ v8i cat(v4i lo, v4i hi) { return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7); }
+
+// NT weight tiles per wave in SG scale groups (tile j uses scale group j / (NT/SG)).
+template <int NT, int SG>
+__device__ __forceinline__ void load_frag(Frag<NT>& f, const uint8_t* const (&wrow)[NT], const float* const (&swp)[SG],
+                                          const uint8_t* xrow, const float* xsrow, int kb) {
+#pragma unroll
+  for (int j = 0; j < NT; j++) {
+    const v4i* p = (const v4i*)(wrow[j] + (size_t)kb * 128);
+    f.w[j][0] = __builtin_nontemporal_load(p);
+    f.w[j][1] = __builtin_nontemporal_load(p + 1);
+  }
+  const v4i* px = (const v4i*)(xrow + (size_t)kb * 128);
+  f.x[0] = px[0];
+  f.x[1] = px[1];
+  f.sa = xsrow[kb];
+#pragma unroll
+  for (int g = 0; g < SG; g++) f.sw[g] = swp[g][kb];
+}
+
+template <int NT, int SG>
+__device__ __forceinline__ void mma_frag(const Frag<NT>& f, v4f (&acc)[NT]) {
+  const v8i b = cat(f.x[0], f.x[1]);
+  float s[SG];
+#pragma unroll
+  for (int g = 0; g < SG; g++) s[g] = f.sa * f.sw[g];
+#pragma unroll
+  for (int j = 0; j < NT; j++) {
+    const v4f zero = {0.f, 0.f, 0.f, 0.f};
+    v4f p = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(cat(f.w[j][0], f.w[j][1]), b, zero, 0, 0, 0, 0, 0, 0);
+    const float sj = s[j / (NT / SG)];
+#pragma unroll
+    for (int i = 0; i < 4; i++) acc[j][i] = fmaf(p[i], sj, acc[j][i]);
+  }
+}
+
+template <int NT, int SG>
+__device__ __forceinline__ void stream_mainloop(const uint8_t* const (&wrow)[NT], const float* const (&swp)[SG],
+                                                const uint8_t* xrow, const float* xsrow, int nkb, v4f (&acc)[NT]) {
+  Frag<NT> f0[kU], f1[kU];
+#pragma unroll
+  for (int u = 0; u < kU; u++)
+    if (u < nkb) load_frag<NT, SG>(f0[u], wrow, swp, xrow, xsrow, u);
+  for (int kb0 = 0; kb0 < nkb; kb0 += 2 * kU) {
+#pragma unroll
+    for (int u = 0; u < kU; u++)
+      if (kb0 + kU + u < nkb) load_frag<NT, SG>(f1[u], wrow, swp, xrow, xsrow, kb0 + kU + u);
+#pragma unroll
+    for (int u = 0; u < kU; u++)
+      if (kb0 + u < nkb) mma_frag<NT, SG>(f0[u], acc);
+#pragma unroll
+    for (int u = 0; u < kU; u++)
+      if (kb0 + 2 * kU + u < nkb) load_frag<NT, SG>(f0[u], wrow, swp, xrow, xsrow, kb0 + 2 * kU + u);
+#pragma unroll
+    for (int u = 0; u < kU; u++)
+      if (kb0 + kU + u < nkb) mma_frag<NT, SG>(f1[u], acc);
+  }
+}
+
+// Task = (expert slot e, block jb of 128 h columns): gate rows jb*128.., up rows I + jb*128..
+// Wave w owns h columns jb*128 + w*32 + {0..31}: tiles 0,1 gate, tiles 2,3 up.
+__global__ __launch_bounds__(kStreamThreads, 2) void gemm1_fp8_stream_kernel(
+    const dwdp_expert_ptrs* __restrict__ table, const int32_t* __restrict__ offsets, const int32_t* __restrict__ perm,
+    const uint8_t* __restrict__ xq, const float* __restrict__ xs, uint8_t* __restrict__ hq, float* __restrict__ hs,
+    int E, int T, int H, int I, int K) {
+  __shared__ float amax_s[4][16];
+  const int njb = I / 128;
+  const int e = blockIdx.x / njb;
+  const int jb = blockIdx.x - e * njb;
+  const int r0 = offsets[e];
+  const int r1 = offsets[e + 1];
+  if (r1 <= r0) return;  // expert without tokens: its weights are never touched
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 15, lq = lane >> 4;
+  const int nkb = H / 128;
+  const uint8_t* w13 = (const uint8_t*)table[e].w13;
+  const float* s13 = table[e].s13;
+  const uint8_t* wrow[4];
+#pragma unroll
+  for (int j = 0; j < 4; j++) {
+    int n = (j < 2 ? 0 : I) + jb * 128 + wave * 32 + (j & 1) * 16 + lr;
+    wrow[j] = w13 + (size_t)n * H + lq * 32;
+  }
+  const float* swp[2] = {s13 + (size_t)jb * nkb, s13 + (size_t)(njb + jb) * nkb};
+
+  for (int rt = r0; rt < r1; rt += 16) {
+    const int r = rt + lr;
+    const int rc = min(r, r1 - 1);  // surplus columns repeat the last row and are not stored
+    const int tok = (e < E) ? perm[rc] / K : rc - T * K;
+    const uint8_t* xrow = xq + (size_t)tok * H + lq * 32;
+    const float* xsrow = xs + (size_t)tok * nkb;
+    v4f acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; j++) acc[j] = (v4f){0.f, 0.f, 0.f, 0.f};
+    stream_mainloop<4, 2>(wrow, swp, xrow, xsrow, nkb, acc);
+
+    float h[2][4];
+    float amax = 0.f;
+#pragma unroll
+    for (int j = 0; j < 2; j++)
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        float g = acc[j][i], u = acc[2 + j][i];
+        float v = g / (1.f + __expf(-g)) * u;
+        h[j][i] = v;
+        amax = fmaxf(amax, fabsf(v));
+      }
+    amax = fmaxf(amax, __shfl_xor(amax, 16));
+    amax = fmaxf(amax, __shfl_xor(amax, 32));
+    if (lq == 0) amax_s[wave][lr] = amax;
+    __syncthreads();
+    amax = fmaxf(fmaxf(amax_s[0][lr], amax_s[1][lr]), fmaxf(amax_s[2][lr], amax_s[3][lr]));
+    const float scale = amax > 0.f ? amax / 448.f : 1.f;
+    if (r < r1) {
+#pragma unroll
+      for (int j = 0; j < 2; j++) {
+        uint32_t q = pack_fp8x4(h[j][0] / scale, h[j][1] / scale, h[j][2] / scale, h[j][3] / scale);
+        *(uint32_t*)(hq + (size_t)r * I + jb * 128 + wave * 32 + j * 16 + lq * 4) = q;
+      }
+      if (wave == 0 && lq == 0) hs[(size_t)r * njb + jb] = scale;
+    }
+    __syncthreads();  // amax_s is reused by the next token tile
+  }
+}
+
+// Task = (expert slot e, block nb of 128 output rows).  Wave w owns rows nb*128 + w*32 + {0..31}.
+__global__ __launch_bounds__(kStreamThreads, 2) void gemm2_fp8_stream_kernel(
+    const dwdp_expert_ptrs* __restrict__ table, const int32_t* __restrict__ offsets, const uint8_t* __restrict__ hq,
+    const float* __restrict__ hs, uint16_t* __restrict__ yp, int H, int I) {
+  const int nnb = H / 128;
+  const int e = blockIdx.x / nnb;
+  const int nb = blockIdx.x - e * nnb;
+  const int r0 = offsets[e];
+  const int r1 = offsets[e + 1];
+  if (r1 <= r0) return;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 15, lq = lane >> 4;
+  const int nkb = I / 128;
+  const uint8_t* w2 = (const uint8_t*)table[e].w2;
+  const float* s2 = table[e].s2;
+  const uint8_t* wrow[2];
+#pragma unroll
+  for (int j = 0; j < 2; j++) wrow[j] = w2 + (size_t)(nb * 128 + wave * 32 + j * 16 + lr) * I + lq * 32;
+  const float* swp[1] = {s2 + (size_t)nb * nkb};
+
+  for (int rt = r0; rt < r1; rt += 16) {
+    const int r = rt + lr;
+    const int rc = min(r, r1 - 1);
+    const uint8_t* xrow = hq + (size_t)rc * I + lq * 32;
+    const float* xsrow = hs + (size_t)rc * nkb;
+    v4f acc[2];
+    acc[0] = (v4f){0.f, 0.f, 0.f, 0.f};
+    acc[1] = (v4f){0.f, 0.f, 0.f, 0.f};
+    stream_mainloop<2, 1>(wrow, swp, xrow, xsrow, nkb, acc);
+    if (r < r1) {
+#pragma unroll
+      for (int j = 0; j < 2; j++) {
+        uint2 o;
+        o.x = (uint32_t)f32_to_bf16(acc[j][0]) | ((uint32_t)f32_to_bf16(acc[j][1]) << 16);
+        o.y = (uint32_t)f32_to_bf16(acc[j][2]) | ((uint32_t)f32_to_bf16(acc[j][3]) << 16);
+        *(uint2*)(yp + (size_t)r * H + nb * 128 + wave * 32 + j * 16 + lq * 4) = o;
+      }
+    }
+  }
+}
+
+void launch_gemm1_fp8(const GemmArgs& a, const uint8_t* xq, const float* xs, uint8_t* hq, float* hs,
+                      hipStream_t stream) {
+  if (a.T <= 0) return;
+  dim3 grid(a.n_slots * (a.I / 128));
+  hipLaunchKernelGGL(gemm1_fp8_stream_kernel, grid, dim3(kStreamThreads), 0, stream, a.table, a.offsets, a.perm, xq,
+                     xs, hq, hs, a.E, a.T, a.H, a.I, a.K);
+}
+
+void launch_gemm2_fp8(const GemmArgs& a, const uint8_t* hq, const float* hs, void* yp, hipStream_t stream) {
+  if (a.T <= 0) return;
+  dim3 grid(a.n_slots * (a.H / 128));
+  hipLaunchKernelGGL(gemm2_fp8_stream_kernel, grid, dim3(kStreamThreads), 0, stream, a.table, a.offsets, hq, hs,
+                     (uint16_t*)yp, a.H, a.I);
+}
+
+// ------------------------------------------------------------------------------ bf16 weights
+// Same task decomposition for bf16 weights and activations, no scales.  GEMM-1 multiplies
+// exact bf16 operands on v_mfma_f32_16x16x32_bf16; h and the down projection stay fp32
+// (v_mfma_f32_16x16x4_f32 with the bf16 weights widened in registers) so that the only
+// rounding of the layer is the final one to bf16.  Serves the small bf16 configuration;
+// not tuned.
+
+__global__ __launch_bounds__(kStreamThreads) void gemm1_bf16_kernel(const dwdp_expert_ptrs* __restrict__ table,
+                                                                    const int32_t* __restrict__ offsets,
+                                                                    const int32_t* __restrict__ perm,
+                                                                    const uint16_t* __restrict__ x,
+                                                                    float* __restrict__ h, int E, int T, int H,
+                                                                    int I, int K) {
+  const int njb = I / 128;
+  const int e = blockIdx.x / njb;
+  const int jb = blockIdx.x - e * njb;
+  const int r0 = offsets[e];
+  const int r1 = offsets[e + 1];
+  if (r1 <= r0) return;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 15, lq = lane >> 4;
+  const uint16_t* w13 = (const uint16_t*)table[e].w13;
+  const uint16_t* wrow[4];
+#pragma unroll
+  for (int j = 0; j < 4; j++) {
+    int n = (j < 2 ? 0 : I) + jb * 128 + wave * 32 + (j & 1) * 16 + lr;
+    wrow[j] = w13 + (size_t)n * H + lq * 8;
+  }
+  for (int rt = r0; rt < r1; rt += 16) {
+    const int r = rt + lr;
+    const int rc = min(r, r1 - 1);
+    const int tok = (e < E) ? perm[rc] / K : rc - T * K;
+    const uint16_t* xrow = x + (size_t)tok * H + lq * 8;
+    v4f acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; j++) acc[j] = (v4f){0.f, 0.f, 0.f, 0.f};
+    for (int k = 0; k < H; k += 32) {
+      const v8bf b = *(const v8bf*)(xrow + k);
+#pragma unroll
+      for (int j = 0; j < 4; j++)
+        acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const v8bf*)(wrow[j] + k), b, acc[j], 0, 0, 0);
+    }
+    if (r < r1) {
+#pragma unroll
+      for (int j = 0; j < 2; j++) {
+        v4f v;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+          float g = acc[j][i], u = acc[2 + j][i];
+          v[i] = g / (1.f + expf(-g)) * u;
+        }
+        *(v4f*)(h + (size_t)r * I + jb * 128 + wave * 32 + j * 16 + lq * 4) = v;
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(kStreamThreads) void gemm2_bf16_kernel(const dwdp_expert_ptrs* __restrict__ table,
+                                                                    const int32_t* __restrict__ offsets,
+                                                                    const float* __restrict__ h,
+                                                                    float* __restrict__ yp, int H, int I) {
+  const int nnb = H / 128;
+  const int e = blockIdx.x / nnb;
+  const int nb = blockIdx.x - e * nnb;
+  const int r0 = offsets[e];
+  const int r1 = offsets[e + 1];
+  if (r1 <= r0) return;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 15, lq = lane >> 4;
+  const uint16_t* w2 = (const uint16_t*)table[e].w2;
+  const uint16_t* wrow[2];
+#pragma unroll
+  for (int j = 0; j < 2; j++) wrow[j] = w2 + (size_t)(nb * 128 + wave * 32 + j * 16 + lr) * I + lq * 8;
+  for (int rt = r0; rt < r1; rt += 16) {
+    const int r = rt + lr;
+    const int rc = min(r, r1 - 1);
+    const float* hrow = h + (size_t)rc * I + lq * 8;
+    v4f acc[2];
+    acc[0] = (v4f){0.f, 0.f, 0.f, 0.f};
+    acc[1] = (v4f){0.f, 0.f, 0.f, 0.f};
+    for (int k = 0; k < I; k += 32) {
+      // lane group lq covers k + lq*8 .. +8 of this 32-wide chunk on both operands
+      const v4f b0 = *(const v4f*)(hrow + k);
+      const v4f b1 = *(const v4f*)(hrow + k + 4);
+#pragma unroll
+      for (int j = 0; j < 2; j++) {
+        const v4i raw = *(const v4i*)(wrow[j] + k);
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+          uint32_t u = (uint32_t)raw[i >> 1];
+          float a = __uint_as_float((i & 1) ? (u & 0xFFFF0000u) : (u << 16));
+          float b = i < 4 ? b0[i] : b1[i - 4];
+          acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[j], 0, 0, 0);
+        }
+      }
+    }
+    if (r < r1) {
+#pragma unroll
+      for (int j = 0; j < 2; j++) *(v4f*)(yp + (size_t)r * H + nb * 128 + wave * 32 + j * 16 + lq * 4) = acc[j];
+    }
+  }
+}
+
+void launch_gemm1_bf16(const GemmArgs& a, const void* x, void* h, hipStream_t stream) {
+  if (a.T <= 0) return;
+  dim3 grid(a.n_slots * (a.I / 128));
+  hipLaunchKernelGGL(gemm1_bf16_kernel, grid, dim3(kStreamThreads), 0, stream, a.table, a.offsets, a.perm,
+                     (const uint16_t*)x, (float*)h, a.E, a.T, a.H, a.I, a.K);
+}
+
+void launch_gemm2_bf16(const GemmArgs& a, const void* h, void* yp, hipStream_t stream) {
+  if (a.T <= 0) return;
+  dim3 grid(a.n_slots * (a.H / 128));
+  hipLaunchKernelGGL(gemm2_bf16_kernel, grid, dim3(kStreamThreads), 0, stream, a.table, a.offsets, (const float*)h,
+                     (float*)yp, a.H, a.I);
+}
+
+}  // namespace dwdp

@@ -1,0 +1,111 @@
+// Activation quantisation (bf16 -> e4m3 with one fp32 scale per token per 128 elements)
+// and the weighted combine of the expert outputs.  Both are pure HBM streams: 16-byte
+// loads per lane, reductions inside 16-lane groups, no LDS.
+#include "dwdp_kernels.h"
+
+namespace dwdp {
+
+// 16 lanes own one 128-element group (8 bf16 each); a wave handles 4 groups per step.
+__global__ __launch_bounds__(256) void quant_act_kernel(const uint16_t* __restrict__ x, long n_groups,
+                                                        uint8_t* __restrict__ xq, float* __restrict__ xs) {
+  long g = ((long)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
+  const int sub = threadIdx.x & 15;
+  const bool live = g < n_groups;
+  if (!live) g = n_groups - 1;  // keep the 16-lane reductions convergent
+  const v4i raw = *(const v4i*)(x + g * 128 + sub * 8);
+  float v[8];
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    uint32_t u = (uint32_t)raw[i];
+    v[2 * i] = __uint_as_float(u << 16);
+    v[2 * i + 1] = __uint_as_float(u & 0xFFFF0000u);
+  }
+  float amax = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; i++) amax = fmaxf(amax, fabsf(v[i]));
+#pragma unroll
+  for (int off = 8; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+  const float scale = amax > 0.f ? amax / 448.f : 1.f;
+  uint32_t lo = pack_fp8x4(v[0] / scale, v[1] / scale, v[2] / scale, v[3] / scale);
+  uint32_t hi = pack_fp8x4(v[4] / scale, v[5] / scale, v[6] / scale, v[7] / scale);
+  if (live) {
+    uint2 o;
+    o.x = lo;
+    o.y = hi;
+    *(uint2*)(xq + g * 128 + sub * 8) = o;
+    if (sub == 0) xs[g] = scale;
+  }
+}
+
+void launch_quant_act(const void* x, int T, int H, uint8_t* xq, float* xs, hipStream_t stream) {
+  long n_groups = (long)T * (H / kBlockScale);
+  if (n_groups <= 0) return;
+  long threads = n_groups * 16;
+  dim3 grid((unsigned)((threads + 255) / 256));
+  hipLaunchKernelGGL(quant_act_kernel, grid, dim3(256), 0, stream, (const uint16_t*)x, n_groups, xq, xs);
+}
+
+// One block per token; each thread owns 8 consecutive columns per step.  The K routed rows
+// are added in slot order k = 0..K-1, then the shared expert's row: deterministic.
+// YP32 = false: yp is bf16 (FP8-weight path); true: yp is fp32 (bf16-weight path).
+template <bool YP32>
+__global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ yp_,
+                                                      const int32_t* __restrict__ inv_perm,
+                                                      const float* __restrict__ topk_w, int T, int H, int K,
+                                                      int has_shared, uint16_t* __restrict__ y) {
+  __shared__ int32_t row_s[33];
+  __shared__ float w_s[33];
+  const int t = blockIdx.x;
+  if ((int)threadIdx.x < K) {
+    row_s[threadIdx.x] = inv_perm[(size_t)t * K + threadIdx.x];
+    w_s[threadIdx.x] = topk_w[(size_t)t * K + threadIdx.x];
+  }
+  if ((int)threadIdx.x == K && has_shared) {
+    row_s[K] = T * K + t;
+    w_s[K] = 1.f;
+  }
+  __syncthreads();
+  const int n = K + (has_shared ? 1 : 0);
+  for (int c = threadIdx.x * 8; c < H; c += blockDim.x * 8) {
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int k = 0; k < n; k++) {
+      const float wk = w_s[k];
+      if (YP32) {
+        const float* p = (const float*)yp_ + (size_t)row_s[k] * H + c;
+        const v4f a = *(const v4f*)p;
+        const v4f b = *(const v4f*)(p + 4);
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+          acc[i] = fmaf(wk, a[i], acc[i]);
+          acc[4 + i] = fmaf(wk, b[i], acc[4 + i]);
+        }
+      } else {
+        const v4i raw = *(const v4i*)((const uint16_t*)yp_ + (size_t)row_s[k] * H + c);
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+          uint32_t u = (uint32_t)raw[i];
+          acc[2 * i] = fmaf(wk, __uint_as_float(u << 16), acc[2 * i]);
+          acc[2 * i + 1] = fmaf(wk, __uint_as_float(u & 0xFFFF0000u), acc[2 * i + 1]);
+        }
+      }
+    }
+    v4i o;
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+      o[i] = (int)((uint32_t)f32_to_bf16(acc[2 * i]) | ((uint32_t)f32_to_bf16(acc[2 * i + 1]) << 16));
+    *(v4i*)(y + (size_t)t * H + c) = o;
+  }
+}
+
+void launch_combine(const void* yp, bool yp_fp32, const int32_t* inv_perm, const float* topk_w, int T, int H, int K,
+                    int has_shared, void* y, hipStream_t stream) {
+  if (T <= 0) return;
+  if (yp_fp32)
+    hipLaunchKernelGGL(combine_kernel<true>, dim3(T), dim3(256), 0, stream, yp, inv_perm, topk_w, T, H, K, has_shared,
+                       (uint16_t*)y);
+  else
+    hipLaunchKernelGGL(combine_kernel<false>, dim3(T), dim3(256), 0, stream, yp, inv_perm, topk_w, T, H, K,
+                       has_shared, (uint16_t*)y);
+}
+
+}  // namespace dwdp

@@ -1,0 +1,40 @@
+"""Shared test plumbing: tensor <-> numpy conversion for the oracle, GPU layer driver."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import moe_oracle as mo
+from paper_2604_01621_amd import inputs
+
+
+def experts_numpy(w: inputs.ExpertWeights, only=None):
+    """Oracle-side view of expert weights (host copies); `only` = iterable of slots to convert."""
+    out = [None] * w.n
+    for e in (range(w.n) if only is None else only):
+        if w.s13 is None:
+            out[e] = mo.ExpertNumpy(w.w13[e].float().cpu().numpy(), w.w2[e].float().cpu().numpy())
+        else:
+            out[e] = mo.ExpertNumpy(w.w13[e].cpu().numpy(), w.w2[e].cpu().numpy(), w.s13[e].cpu().numpy(),
+                                    w.s2[e].cpu().numpy())
+    return out
+
+
+def to_np(t):
+    if t is None:
+        return None
+    if t.dtype == torch.bfloat16:
+        return t.float().cpu().numpy()
+    return t.cpu().numpy()
+
+
+def tolerance(cfg) -> float:
+    """Parity bar: max |y - ref| / max |ref| <= 2e-2 with FP8 weights, 5e-3 with bf16 weights."""
+    return 2e-2 if cfg.w_dtype == inputs.W_FP8 else 5e-3
+
+
+def gpu_forward(ctx, cfg, x, logits, bias, table, layer=0):
+    y = torch.empty(x.shape[0], cfg.H, dtype=torch.bfloat16, device=x.device)
+    ctx.dwdp_moe_forward(layer, x, logits, bias, table, y)
+    torch.cuda.synchronize()
+    return y
