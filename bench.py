@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Benchmark of the DWDP MoE-layer hot path on one MI355X.
+
+A step is one dwdp_moe_forward (route -> permute -> quantise -> grouped GEMM gate/up+SwiGLU
+-> grouped GEMM down -> combine) over one batch of seeded synthetic tokens with all inputs
+and weights resident in HBM.  Default workload: the DeepSeek-R1-shaped decode layer, T=64.
+Prints ONE JSON line (see the fields below); `roofline` is for the dominant kernel measured
+with HIP events on the compute stream inside the timed region; `cpu_baseline` is the CPU
+oracle timed on a bounded sample of the same workload on this host.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+FP8_PEAK_TFLOPS = 5000.0     # MI355X dense FP8 MFMA, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="decode", choices=["decode", "prefill", "skew", "pipeline", "tiny"])
+    ap.add_argument("--T", type=int, default=None, help="override the workload's token count")
+    ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=2)
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, x, logits, bias, w, n_tok):
+    """Time the oracle (as it stands) on the first n_tok tokens of the workload."""
+    import numpy as np
+    from oracle import moe_oracle as mo
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    spec = mo.spec_from(cfg)
+    lg = logits.float().cpu().numpy()
+    bs = None if bias is None else bias.float().cpu().numpy()
+    xs = x.float().cpu().numpy()
+    ids, _ = mo.route(lg[:n_tok], bs, spec)
+    need = sorted(set(int(e) for e in ids.reshape(-1)) | ({cfg.E} if cfg.has_shared else set()))
+    ex = [None] * w.n
+    for e in need:     # host copies of the bytes are input staging, not oracle work
+        if w.s13 is None:
+            ex[e] = mo.ExpertNumpy(w.w13[e].float().cpu().numpy(), w.w2[e].float().cpu().numpy())
+        else:
+            ex[e] = mo.ExpertNumpy(w.w13[e].cpu().numpy(), w.w2[e].cpu().numpy(), w.s13[e].cpu().numpy(),
+                                   w.s2[e].cpu().numpy())
+    t0 = time.perf_counter()
+    ref = mo.moe_forward(xs[:n_tok], lg[:n_tok], bs, ex, spec)
+    dt = time.perf_counter() - t0
+    return {"value": n_tok / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {n_tok} tokens of the workload ({len(need)} experts dequantised), {dt:.1f} s"}, ref
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2604_01621_amd import binding, inputs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    if args.workload == "pipeline":
+        from paper_2604_01621_amd import pipeline_bench
+        out = pipeline_bench.run(args)
+        print(json.dumps(out))
+        return
+
+    cfg, x, logits, bias = inputs.make_layer_inputs(args.workload, args.seed, device=dev, T=args.T)
+    w = inputs.make_expert_weights(cfg, args.seed, device=dev)
+    stream = torch.cuda.Stream()
+    ctx = binding.Context(cfg, stream=stream)
+    wp = ctx.pack_experts(w)          # one-off weight preparation, outside the timed region
+    table = binding.expert_table(wp)
+    y = torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device=dev)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        ctx.dwdp_moe_forward(0, x, logits, bias, table, y)
+    torch.cuda.synchronize()
+    ctx.dwdp_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ctx.dwdp_moe_forward(0, x, logits, bias, table, y)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    stage_ms, n_calls = ctx.dwdp_profile_read()
+    ctx.dwdp_profile_enable(False)
+    stage_ms = {k: v / max(n_calls, 1) for k, v in stage_ms.items()}
+
+    n_off = cfg.E + 1 + cfg.has_shared
+    off = ctx.workspace("offsets", (n_off,), torch.int32).cpu().numpy()
+    counts = off[1:] - off[:-1]
+    active = int((counts > 0).sum())
+    pairs = int(counts.sum())
+    ms_per_step = dt / args.steps * 1e3
+
+    fp8 = cfg.w_dtype == inputs.W_FP8
+    el = 1 if fp8 else 2
+    b13 = 2 * cfg.I * cfg.H * el + (4 * (2 * cfg.I // 128) * (cfg.H // 128) if fp8 else 0)
+    b2 = cfg.H * cfg.I * el + (4 * (cfg.H // 128) * (cfg.I // 128) if fp8 else 0)
+    flops1 = 2 * 2 * cfg.I * cfg.H * pairs
+    flops2 = 2 * cfg.I * cfg.H * pairs
+    weight_bound = args.workload in ("decode", "skew", "tiny")
+    if weight_bound:
+        ach = active * b13 / (stage_ms["gemm1"] * 1e-3) / 1e9
+        roof = {"bound": "hbm", "kernel": "gemm1 (gate/up + SwiGLU)", "achieved": ach, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                "algorithmic_bytes_per_launch": active * b13, "avg_launch_ms": stage_ms["gemm1"]}
+        ach2 = active * b2 / (stage_ms["gemm2"] * 1e-3) / 1e9
+        roof2 = {"bound": "hbm", "kernel": "gemm2 (down)", "achieved": ach2, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                 "frac": ach2 / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": active * b2,
+                 "avg_launch_ms": stage_ms["gemm2"]}
+    else:
+        ach = flops1 / (stage_ms["gemm1"] * 1e-3) / 1e12
+        roof = {"bound": "mfma", "kernel": "gemm1 (gate/up + SwiGLU)", "achieved": ach, "peak": FP8_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": ach / FP8_PEAK_TFLOPS, "traffic": None,
+                "algorithmic_flops_per_launch": flops1, "avg_launch_ms": stage_ms["gemm1"]}
+        ach2 = flops2 / (stage_ms["gemm2"] * 1e-3) / 1e12
+        roof2 = {"bound": "mfma", "kernel": "gemm2 (down)", "achieved": ach2, "peak": FP8_PEAK_TFLOPS,
+                 "unit": "TFLOP/s", "frac": ach2 / FP8_PEAK_TFLOPS, "algorithmic_flops_per_launch": flops2,
+                 "avg_launch_ms": stage_ms["gemm2"]}
+
+    out = {
+        "metric": "moe_layer_tokens_per_s", "value": cfg.T / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp8_e4m3" if fp8 else "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: DeepSeek-R1-shaped MoE layer" if args.workload != "tiny"
+                   else "tiny bf16 MoE layer", "T": cfg.T, "H": cfg.H, "I": cfg.I, "E": cfg.E, "K": cfg.K,
+                   "shared_experts": cfg.has_shared, "active_expert_slots": active, "token_expert_pairs": pairs,
+                   "weights": "FP8 e4m3 + fp32 128x128 block scales, all resident" if fp8 else "bf16, all resident"},
+        "roofline": roof, "roofline_gemm2": roof2, "stage_ms": stage_ms,
+        "layer_weight_gbs": active * (b13 + b2) / (ms_per_step * 1e-3) / 1e9,
+    }
+    if not args.no_cpu_baseline:
+        n_tok = min(args.cpu_sample_tokens, cfg.T)
+        cb, ref = cpu_baseline(cfg, x, logits, bias, w, n_tok)
+        out["cpu_baseline"] = cb
+        from oracle import moe_oracle as mo
+        err, l2 = mo.error_metrics(y[:n_tok].float().cpu().numpy(), ref)
+        out["sample_max_rel_err"] = err
+    print(json.dumps(out))
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()

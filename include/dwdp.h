@@ -66,9 +66,11 @@ typedef struct {
  * buffer; the kernels do not care.  Slot e < E is routed expert e, slot E the shared one.
  *   w13  [2I, H]  rows 0..I-1 gate projection, rows I..2I-1 up projection
  *   w2   [H, I]   down projection
- *   FP8:  1 byte/element; s13 fp32 [2I/128, H/128], s2 fp32 [H/128, I/128]: one scale per
- *         128x128 block, weight = decode(byte) * scale.  Pointers 16-byte aligned.
- *   bf16: 2 bytes/element; s13 = s2 = NULL.
+ *   FP8:  1 byte/element, stored TILE-MAJOR as written by dwdp_pack_fp8_weight (the
+ *         kernels stream whole 2 KiB tiles); s13 fp32 [2I/128, H/128], s2 fp32
+ *         [H/128, I/128] row-major: one scale per 128x128 block of the logical matrix,
+ *         weight = decode(byte) * scale.  Pointers 16-byte aligned.
+ *   bf16: 2 bytes/element, plain row-major; s13 = s2 = NULL.
  */
 typedef struct {
   const void* w13;
@@ -144,6 +146,20 @@ dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void* x, const 
  */
 dwdp_status dwdp_prefetch_layer(dwdp_ctx* ctx, int32_t layer, const void* const* src, void* const* dst,
                                 const size_t* bytes, int32_t n_peers, int32_t n_params, size_t slice_bytes);
+
+/*
+ * Weight preparation, done once when weights are loaded (on the owner of every expert,
+ * so that resident and peer copies are byte-identical and prefetch stays a plain copy):
+ * rearrange a row-major FP8 matrix src [rows, cols] into the tile-major layout the FP8
+ * grouped GEMM streams.  Tiles are 16 rows x 128 columns = 2 KiB, ordered row-of-tiles
+ * first; inside a tile byte half*1024 + (q*16 + r)*16 + b holds element (row r,
+ * column q*32 + half*16 + b), r < 16, q < 4, half < 2, b < 16 -- the order in which the
+ * 64 lanes of a wavefront feed a 16x16x128 matrix-core operand, so every load
+ * instruction of a wave covers 1 KiB of contiguous memory.  rows % 16 == 0,
+ * cols % 128 == 0 (DWDP_ESHAPE otherwise); src and dst must not overlap.  Enqueued on the
+ * compute stream.
+ */
+dwdp_status dwdp_pack_fp8_weight(dwdp_ctx* ctx, const void* src, void* dst, int64_t rows, int64_t cols);
 
 /*
  * Host-only: the copy plan dwdp_prefetch_layer would issue, written to HOST arrays of

@@ -59,6 +59,7 @@ def _load() -> C.CDLL:
                                          C.POINTER(vp), C.POINTER(vp), C.POINTER(sz), sz, C.POINTER(sz)]
     lib.dwdp_merge_experts.argtypes = [vp, C.POINTER(dwdp_expert_ptrs), i32, vp, vp, vp, vp,
                                        C.POINTER(dwdp_expert_ptrs)]
+    lib.dwdp_pack_fp8_weight.argtypes = [vp, vp, vp, C.c_int64, C.c_int64]
     lib.dwdp_profile_enable.argtypes = [vp, i32]
     lib.dwdp_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32)]
     lib.dwdp_workspace_ptr.argtypes = [vp, i32]
@@ -164,6 +165,30 @@ class Context:
         self._check(lib.dwdp_merge_experts(self.h, src, n, _ptr(w13_out), _ptr(s13_out), _ptr(w2_out), _ptr(s2_out),
                                            dst))
         return merged
+
+    def dwdp_pack_fp8_weight(self, src: torch.Tensor, dst: torch.Tensor):
+        """src uint8 [..., rows, cols] row-major matrices -> dst (same shape) tile-major, matrix by matrix."""
+        assert src.shape == dst.shape and src.dtype == torch.uint8 and dst.dtype == torch.uint8
+        rows, cols = src.shape[-2], src.shape[-1]
+        n = src.numel() // (rows * cols) if rows * cols else 0
+        s2, d2 = src.reshape(n, rows, cols), dst.reshape(n, rows, cols)
+        for i in range(n):
+            self._check(lib.dwdp_pack_fp8_weight(self.h, _ptr(s2[i]), _ptr(d2[i]), rows, cols))
+
+    def pack_experts(self, w: ExpertWeights) -> ExpertWeights:
+        """Device copy of `w` in the layout the kernels read: FP8 codes tile-major, scales and
+        bf16 weights unchanged (shared, not copied)."""
+        if w.s13 is None:
+            return w
+        p13, p2 = torch.empty_like(w.w13), torch.empty_like(w.w2)
+        torch.cuda.synchronize()      # `w` may still be being written on another stream
+        self.dwdp_pack_fp8_weight(w.w13, p13)
+        self.dwdp_pack_fp8_weight(w.w2, p2)
+        if self.stream is not None:
+            self.stream.synchronize()
+        else:
+            torch.cuda.synchronize()
+        return ExpertWeights(p13, p2, w.s13, w.s2)
 
     def dwdp_profile_enable(self, on: bool):
         self._check(lib.dwdp_profile_enable(self.h, 1 if on else 0))

@@ -330,6 +330,18 @@ extern "C" dwdp_status dwdp_merge_experts(dwdp_ctx* ctx, const dwdp_expert_ptrs*
   return DWDP_OK;
 }
 
+extern "C" dwdp_status dwdp_pack_fp8_weight(dwdp_ctx* ctx, const void* src, void* dst, int64_t rows, int64_t cols) {
+  if (!ctx) return DWDP_EINVAL;
+  if (rows < 0 || cols < 0) return fail(ctx, DWDP_EINVAL, "dwdp_pack_fp8_weight: negative size");
+  if (rows % 16 || cols % 128 || cols > (1 << 30))
+    return fail(ctx, DWDP_ESHAPE, "dwdp_pack_fp8_weight: rows must be a multiple of 16 and cols of 128");
+  if (rows * cols == 0) return DWDP_OK;
+  if (!src || !dst || src == dst) return fail(ctx, DWDP_EINVAL, "dwdp_pack_fp8_weight: NULL or aliased pointers");
+  launch_pack_fp8_tiles(src, dst, rows, (int)cols, ctx->compute);
+  HIP_TRY(ctx, hipGetLastError());
+  return DWDP_OK;
+}
+
 extern "C" dwdp_status dwdp_profile_enable(dwdp_ctx* ctx, int32_t on) {
   if (!ctx) return DWDP_EINVAL;
   if (on && ctx->prof_ev.empty()) {

@@ -15,6 +15,7 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 constexpr int kWave = 64;
 constexpr int kBlockScale = 128;  // side of a weight scale block = activation quantisation group
+constexpr int kTileBytes = 2048;   // one packed FP8 weight tile: 16 rows x 128 columns
 
 struct RouteParams {
   int E, K, n_group, topk_group, score_fn;
@@ -45,7 +46,10 @@ struct GemmArgs {
   int n_slots, E, T, H, I, K;
 };
 
-// FP8: h = quant(silu(Xq Wg^T) * (Xq Wu^T)); hq fp8 [rows,I], hs fp32 [rows,I/128]
+// Row-major fp8 [rows, cols] (rows % 16 == 0, cols % 128 == 0) -> tile-major layout of the FP8 GEMMs.
+void launch_pack_fp8_tiles(const void* src, void* dst, long rows, int cols, hipStream_t stream);
+
+// FP8 (weights tile-major): h = quant(silu(Xq Wg^T) * (Xq Wu^T)); hq fp8 [rows,I], hs fp32 [rows,I/128]
 void launch_gemm1_fp8(const GemmArgs& a, const uint8_t* xq, const float* xs, uint8_t* hq, float* hs,
                       hipStream_t stream);
 // FP8: yp = Hq W2^T, bf16 [rows,H]

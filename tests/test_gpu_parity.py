@@ -112,12 +112,30 @@ def test_permute_skewed_histogram(binding):
     ctx.close()
 
 
+def test_pack_fp8_weight_layout(binding):
+    """Tile-major packing against the layout the header documents, written out in numpy."""
+    print("pack layout", flush=True)
+    cfg = inputs.small_fp8_layer(T=1)
+    ctx = binding.Context(cfg)
+    rows, cols = 48, 384
+    g = torch.Generator().manual_seed(0)
+    src = torch.randint(0, 256, (2, rows, cols), generator=g, dtype=torch.int32).to(torch.uint8)
+    dst = torch.zeros_like(src).cuda()
+    ctx.dwdp_pack_fp8_weight(src.cuda(), dst)
+    torch.cuda.synchronize()
+    s = src.numpy()
+    # [m, tr, r, kb, q, half, b] -> [m, tr, kb, half, q, r, b]
+    want = s.reshape(2, rows // 16, 16, cols // 128, 4, 2, 16).transpose(0, 1, 3, 5, 4, 2, 6).reshape(2, rows, cols)
+    np.testing.assert_array_equal(dst.cpu().numpy(), want)
+    ctx.close()
+
+
 def _layer_case(binding, cfg, x, logits, bias, w, check_intermediates=False):
     dev = "cuda"
     wd = inputs.ExpertWeights(w.w13.to(dev), w.w2.to(dev), None if w.s13 is None else w.s13.to(dev),
                               None if w.s2 is None else w.s2.to(dev))
-    table = binding.expert_table(wd)
     ctx = binding.Context(cfg)
+    table = binding.expert_table(ctx.pack_experts(wd))
     xd, ld = x.to(dev), logits.to(dev)
     bd = None if bias is None else bias.to(dev)
     y = gpu_forward(ctx, cfg, xd, ld, bd, table)
@@ -169,6 +187,17 @@ def test_layer_small_fp8(binding, T):
     _layer_case(binding, cfg, x, logits, bias, w, check_intermediates=True)
 
 
+@pytest.mark.parametrize("H,I,T", [(1536, 1024, 37), (1408, 640, 20)])
+def test_layer_fp8_long_k(binding, H, I, T):
+    """K loops of several pipeline rounds plus a remainder (H/128 = 12 or 11, I/128 = 8 or 5)."""
+    print("layer fp8 long-k", H, I, T, flush=True)
+    cfg = inputs.small_fp8_layer(T=T, H=H, I=I, E=8, K=2, n_group=1, topk_group=1)
+    x = inputs.make_activations(cfg, 21)
+    logits = inputs.make_gate_logits(cfg, x, 21)
+    w = inputs.make_expert_weights(cfg, 21)
+    _layer_case(binding, cfg, x, logits, None, w, check_intermediates=True)
+
+
 def test_layer_small_fp8_no_shared_and_empty(binding):
     print("layer small fp8 no shared / T=0", flush=True)
     cfg = inputs.small_fp8_layer(T=40, has_shared=0, E=32, n_group=4, topk_group=2, K=4, H=384, I=128)
@@ -180,7 +209,7 @@ def test_layer_small_fp8_no_shared_and_empty(binding):
     ctx = binding.Context(cfg)
     wd = inputs.ExpertWeights(w.w13.cuda(), w.w2.cuda(), w.s13.cuda(), w.s2.cuda())
     y = torch.empty(0, cfg.H, dtype=torch.bfloat16, device="cuda")
-    ctx.dwdp_moe_forward(0, x[:0].cuda(), logits[:0].cuda(), None, binding.expert_table(wd), y)
+    ctx.dwdp_moe_forward(0, x[:0].cuda(), logits[:0].cuda(), None, binding.expert_table(ctx.pack_experts(wd)), y)
     torch.cuda.synchronize()
     ctx.close()
 
