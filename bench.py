@@ -31,6 +31,10 @@ def parse():
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2)
+    ap.add_argument("--slice-mib", type=int, default=64, help="pipeline workload: prefetch slice size in MiB")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="after the timed region run one plain device copy of this many MiB (a known-size "
+                         "reference dispatch for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -103,6 +107,14 @@ def main():
     stage_ms, n_calls = ctx.dwdp_profile_read()
     ctx.dwdp_profile_enable(False)
     stage_ms = {k: v / max(n_calls, 1) for k, v in stage_ms.items()}
+
+    if args.calib_copy_mib > 0:
+        src = torch.ones(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     n_off = cfg.E + 1 + cfg.has_shared
     off = ctx.workspace("offsets", (n_off,), torch.int32).cpu().numpy()

@@ -203,6 +203,24 @@ dwdp_status dwdp_profile_enable(dwdp_ctx* ctx, int32_t on);
 dwdp_status dwdp_profile_read(dwdp_ctx* ctx, float* ms_sum, int32_t* n_calls);
 
 /*
+ * Timeline of the two streams, for measuring how much of the staging-copy time is hidden
+ * behind compute (paper Section 2).  While enabled, every dwdp_prefetch_layer records a
+ * DWDP_SPAN_COPY span on the copy stream (first copy issued .. last copy done, i.e. after
+ * the wait for the buffer's previous reader) and every dwdp_moe_forward a DWDP_SPAN_GEMM
+ * span on the compute stream (grouped GEMM-1 start .. GEMM-2 end: the part that reads
+ * expert weights).  dwdp_timeline_enable(on) synchronises both streams, drops old spans
+ * and, when on, sets time zero.  dwdp_timeline_read synchronises both streams and writes
+ * up to cap spans, in issue order, to HOST arrays: kind, layer, start and end in
+ * milliseconds since time zero; *n_out is the number recorded (at most
+ * DWDP_TIMELINE_MAX are kept).
+ */
+enum { DWDP_SPAN_COPY = 0, DWDP_SPAN_GEMM = 1 };
+enum { DWDP_TIMELINE_MAX = 4096 };
+dwdp_status dwdp_timeline_enable(dwdp_ctx* ctx, int32_t on);
+dwdp_status dwdp_timeline_read(dwdp_ctx* ctx, int32_t* kind, int32_t* layer, float* start_ms, float* end_ms,
+                               int32_t cap, int32_t* n_out);
+
+/*
  * Device pointers of the context's workspace for inspection by tests (valid until
  * dwdp_destroy; contents are those of the last dwdp_moe_forward once the stream is idle).
  */

@@ -62,6 +62,9 @@ def _load() -> C.CDLL:
     lib.dwdp_pack_fp8_weight.argtypes = [vp, vp, vp, C.c_int64, C.c_int64]
     lib.dwdp_profile_enable.argtypes = [vp, i32]
     lib.dwdp_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32)]
+    lib.dwdp_timeline_enable.argtypes = [vp, i32]
+    fp, ip = C.POINTER(C.c_float), C.POINTER(i32)
+    lib.dwdp_timeline_read.argtypes = [vp, ip, ip, fp, fp, i32, ip]
     lib.dwdp_workspace_ptr.argtypes = [vp, i32]
     lib.dwdp_workspace_ptr.restype = vp
     lib.dwdp_copy_stream.argtypes = [vp]
@@ -198,6 +201,18 @@ class Context:
         n = C.c_int32(0)
         self._check(lib.dwdp_profile_read(self.h, ms, C.byref(n)))
         return {name: ms[i] for i, name in enumerate(STAGES)}, n.value
+
+    def dwdp_timeline_enable(self, on: bool):
+        self._check(lib.dwdp_timeline_enable(self.h, 1 if on else 0))
+
+    def dwdp_timeline_read(self):
+        """[(kind, layer, start_ms, end_ms), ...] with kind 0 = copy span, 1 = GEMM span."""
+        cap = 4096
+        kind, layer = (C.c_int32 * cap)(), (C.c_int32 * cap)()
+        a, b = (C.c_float * cap)(), (C.c_float * cap)()
+        n = C.c_int32(0)
+        self._check(lib.dwdp_timeline_read(self.h, kind, layer, a, b, cap, C.byref(n)))
+        return [(kind[i], layer[i], a[i], b[i]) for i in range(min(n.value, cap))]
 
     def workspace(self, name: str, shape, dtype) -> torch.Tensor:
         """Copy of a workspace buffer (device-to-device) as a tensor of the given shape/dtype."""

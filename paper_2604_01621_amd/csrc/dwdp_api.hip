@@ -31,6 +31,14 @@ struct dwdp_ctx {
   bool prof = false;
   std::vector<hipEvent_t> prof_ev;
   int prof_calls = 0;
+  // timeline of prefetch copies and GEMM phases (both streams), relative to tl_base
+  struct Span {
+    int kind, layer;
+    hipEvent_t a, b;
+  };
+  bool tl_on = false;
+  hipEvent_t tl_base = nullptr;
+  std::vector<Span> tl;
   std::string err;
 };
 
@@ -136,11 +144,33 @@ extern "C" void dwdp_destroy(dwdp_ctx* c) {
     if (ev) (void)hipEventDestroy(ev);
   for (hipEvent_t ev : c->prof_ev)
     if (ev) (void)hipEventDestroy(ev);
+  for (auto& sp : c->tl) {
+    (void)hipEventDestroy(sp.a);
+    (void)hipEventDestroy(sp.b);
+  }
+  if (c->tl_base) (void)hipEventDestroy(c->tl_base);
   if (c->copy) (void)hipStreamDestroy(c->copy);
   delete c;
 }
 
 extern "C" const char* dwdp_last_error(const dwdp_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_err.c_str(); }
+
+// Open a timeline span on `s`: creates two events, records the first.  Returns the span index or -1.
+static int tl_open(dwdp_ctx* ctx, int kind, int layer, hipStream_t s) {
+  if (!ctx->tl_on || ctx->tl.size() >= (size_t)DWDP_TIMELINE_MAX) return -1;
+  dwdp_ctx::Span sp{kind, layer, nullptr, nullptr};
+  if (hipEventCreate(&sp.a) != hipSuccess) return -1;
+  if (hipEventCreate(&sp.b) != hipSuccess) {
+    (void)hipEventDestroy(sp.a);
+    return -1;
+  }
+  (void)hipEventRecord(sp.a, s);
+  ctx->tl.push_back(sp);
+  return (int)ctx->tl.size() - 1;
+}
+static void tl_close(dwdp_ctx* ctx, int idx, hipStream_t s) {
+  if (idx >= 0) (void)hipEventRecord(ctx->tl[idx].b, s);
+}
 
 static RouteParams route_params(const dwdp_config& c) {
   return RouteParams{c.E, c.K, c.n_group, c.topk_group, c.score_fn, c.routed_scale};
@@ -219,6 +249,7 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
   // Only the grouped GEMMs read expert weights: the wait for the staged experts goes here.
   if (consume) HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->staged_ev[layer], 0));
   if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM1), s));
+  const int span = tl_open(ctx, DWDP_SPAN_GEMM, layer, s);
   if (fp8)
     launch_gemm1_fp8(ga, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
                      (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], s);
@@ -230,6 +261,7 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
                      s);
   else
     launch_gemm2_bf16(ga, ctx->ws[DWDP_WS_HQ], ctx->ws[DWDP_WS_YP], s);
+  tl_close(ctx, span, s);
   // The layer's weights have been read once GEMM-2 is done: release the staging buffer here.
   HIP_TRY(ctx, hipEventRecord(ctx->done_ev[b], s));
   ctx->done_valid[b] = true;
@@ -294,8 +326,10 @@ extern "C" dwdp_status dwdp_prefetch_layer(dwdp_ctx* ctx, int32_t layer, const v
   dwdp_build_copy_plan(src, dst, bytes, n_peers, n_params, slice_bytes, pd.data(), ps.data(), pb.data(), n, &n);
   // double buffering: the buffer is free once its previous reader has finished
   if (ctx->done_valid[b]) HIP_TRY(ctx, hipStreamWaitEvent(ctx->copy, ctx->done_ev[b], 0));
+  const int span = tl_open(ctx, DWDP_SPAN_COPY, layer, ctx->copy);
   for (size_t i = 0; i < n; i++)
     HIP_TRY(ctx, hipMemcpyAsync(pd[i], ps[i], pb[i], hipMemcpyDeviceToDevice, ctx->copy));
+  tl_close(ctx, span, ctx->copy);
   HIP_TRY(ctx, hipEventRecord(ctx->staged_ev[layer], ctx->copy));
   ctx->pending_layer[b] = layer;
   return DWDP_OK;
@@ -368,6 +402,42 @@ extern "C" dwdp_status dwdp_profile_read(dwdp_ctx* ctx, float* ms_sum, int32_t* 
   }
   *n_calls = ctx->prof_calls;
   ctx->prof_calls = 0;
+  return DWDP_OK;
+}
+
+extern "C" dwdp_status dwdp_timeline_enable(dwdp_ctx* ctx, int32_t on) {
+  if (!ctx) return DWDP_EINVAL;
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->compute));
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->copy));
+  for (auto& sp : ctx->tl) {
+    (void)hipEventDestroy(sp.a);
+    (void)hipEventDestroy(sp.b);
+  }
+  ctx->tl.clear();
+  ctx->tl_on = on != 0;
+  if (ctx->tl_on) {
+    if (!ctx->tl_base) HIP_TRY(ctx, hipEventCreate(&ctx->tl_base));
+    HIP_TRY(ctx, hipEventRecord(ctx->tl_base, ctx->compute));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->compute));
+  }
+  return DWDP_OK;
+}
+
+extern "C" dwdp_status dwdp_timeline_read(dwdp_ctx* ctx, int32_t* kind, int32_t* layer, float* start_ms,
+                                          float* end_ms, int32_t cap, int32_t* n_out) {
+  if (!ctx) return DWDP_EINVAL;
+  if (!n_out || cap < 0 || (cap > 0 && (!kind || !layer || !start_ms || !end_ms)))
+    return fail(ctx, DWDP_EINVAL, "dwdp_timeline_read: NULL pointer");
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->compute));
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->copy));
+  const int n = (int)ctx->tl.size();
+  for (int i = 0; i < n && i < cap; i++) {
+    kind[i] = ctx->tl[i].kind;
+    layer[i] = ctx->tl[i].layer;
+    HIP_TRY(ctx, hipEventElapsedTime(&start_ms[i], ctx->tl_base, ctx->tl[i].a));
+    HIP_TRY(ctx, hipEventElapsedTime(&end_ms[i], ctx->tl_base, ctx->tl[i].b));
+  }
+  *n_out = n;
   return DWDP_OK;
 }
 

@@ -1,0 +1,125 @@
+"""Benchmark leg for the split-weight prefetch pipeline workload (4 layers, T=256,
+64 resident + 192 staged experts per layer).  Called by bench.py --workload pipeline."""
+from __future__ import annotations
+
+import time
+
+import torch
+
+from . import binding, inputs, pipeline
+
+HBM_PEAK_GBS = 8000.0
+
+
+def overlap_fraction(spans):
+    """Share of the copy spans' total duration during which some GEMM span is running."""
+    gemm = sorted((a, b) for k, _, a, b in spans if k == 1)
+    merged = []
+    for a, b in gemm:
+        if merged and a <= merged[-1][1]:
+            merged[-1][1] = max(merged[-1][1], b)
+        else:
+            merged.append([a, b])
+    tot = hid = 0.0
+    for k, _, a, b in spans:
+        if k != 0:
+            continue
+        tot += b - a
+        for ga, gb in merged:
+            lo, hi = max(a, ga), min(b, gb)
+            if hi > lo:
+                hid += hi - lo
+    return (hid / tot if tot > 0 else 0.0), tot
+
+
+def run(args):
+    dev = torch.device("cuda:0")
+    cfg = inputs.WORKLOADS["pipeline"] if args.T is None else inputs.WORKLOADS["pipeline"].with_T(args.T)
+    n_layers, n_res, n_peers = 4, 64, 3
+    slice_bytes = getattr(args, "slice_mib", 64) << 20
+    stream = torch.cuda.Stream()
+    ctx = binding.Context(cfg, n_layers=n_layers, stream=stream)
+    layers = pipeline.SplitWeightLayers(ctx, cfg, n_layers, n_res, n_peers, seed=args.seed, device=dev)
+    layers.drop_logical()
+    torch.cuda.empty_cache()
+    xs, lgs, bs, ys = [], [], [], []
+    for l in range(n_layers):
+        x = inputs.make_activations(cfg, args.seed + 10 + l, device=dev)
+        xs.append(x)
+        lgs.append(inputs.make_gate_logits(cfg, x, args.seed + 10 + l))
+        bs.append(inputs.make_bias(cfg, args.seed + 10 + l, device=dev, kind="small"))
+        ys.append(torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device=dev))
+    torch.cuda.synchronize()
+
+    def loop(n_iter, with_prefetch=True):
+        # steady state: the prefetch of the next iteration's layer 0 runs under this iteration's last layer
+        for it in range(n_iter):
+            for l in range(n_layers):
+                if with_prefetch:
+                    nxt = (l + 1) % n_layers
+                    if not (it == n_iter - 1 and l == n_layers - 1):
+                        layers.prefetch(ctx, nxt, slice_bytes)
+                ctx.dwdp_moe_forward(l, xs[l], lgs[l], bs[l], layers.tables[l], ys[l])
+
+    # compute alone (staging already holds valid experts after one warm pass) and copy alone
+    layers.prefetch(ctx, 0, slice_bytes)
+    loop(max(args.warmup, 1))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    loop(args.steps, with_prefetch=False)
+    torch.cuda.synchronize()
+    compute_alone_ms = (time.perf_counter() - t0) * 1e3 / (args.steps * n_layers)
+    t0 = time.perf_counter()
+    n_copy = 4
+    y_dummy = torch.empty(0, cfg.H, dtype=torch.bfloat16, device=dev)
+    for i in range(n_copy):
+        layers.prefetch(ctx, i % 2, slice_bytes)
+        ctx.dwdp_moe_forward(i % 2, xs[0][:0], lgs[0][:0], bs[0], layers.tables[i % 2], y_dummy)   # T=0: consume
+    torch.cuda.synchronize()
+    copy_alone_ms = (time.perf_counter() - t0) * 1e3 / n_copy
+
+    # timed steady-state pipeline
+    layers.prefetch(ctx, 0, slice_bytes)
+    torch.cuda.synchronize()
+    ctx.dwdp_timeline_enable(True)
+    ctx.dwdp_profile_enable(True)
+    t0 = time.perf_counter()
+    loop(args.steps)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    stage_ms, n_calls = ctx.dwdp_profile_read()
+    spans = ctx.dwdp_timeline_read()
+    ctx.dwdp_timeline_enable(False)
+    ctx.dwdp_profile_enable(False)
+    frac, copy_ms_total = overlap_fraction(spans)
+    n_copies = sum(1 for s in spans if s[0] == 0)
+    ms_per_layer = dt * 1e3 / (args.steps * n_layers)
+    stage_ms = {k: v / max(n_calls, 1) for k, v in stage_ms.items()}
+
+    n_off = cfg.E + 2
+    off = ctx.workspace("offsets", (n_off,), torch.int32).cpu().numpy()
+    active = int(((off[1:] - off[:-1]) > 0).sum())
+    eb = inputs.expert_bytes(cfg)
+    b13 = 2 * cfg.I * cfg.H + 4 * (2 * cfg.I // 128) * (cfg.H // 128)
+    ach = active * b13 / (stage_ms["gemm1"] * 1e-3) / 1e9
+    pf_bytes = layers.prefetch_bytes()
+    out = {
+        "metric": "moe_layer_tokens_per_s", "value": cfg.T / (ms_per_layer * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_layer * n_layers,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8_e4m3", "data": "synthetic",
+        "config": {"workload": "pipeline: 4 DeepSeek-R1-shaped MoE layers, 64 resident + 192 staged experts each",
+                   "T": cfg.T, "layers": n_layers, "slice_bytes": slice_bytes, "active_expert_slots": active,
+                   "prefetch_bytes_per_layer": pf_bytes},
+        "ms_per_layer": ms_per_layer, "compute_alone_ms_per_layer": compute_alone_ms,
+        "copy_alone_ms_per_layer": copy_alone_ms, "copy_alone_gbs": pf_bytes / (copy_alone_ms * 1e-3) / 1e9,
+        "overlap": {"copy_time_overlapped_with_gemm_frac": frac,
+                    "avg_copy_ms": copy_ms_total / max(n_copies, 1), "copies": n_copies,
+                    "source": "HIP events on both streams (dwdp_timeline_read)"},
+        "roofline": {"bound": "hbm", "kernel": "gemm1 (gate/up + SwiGLU) under concurrent prefetch", "achieved": ach,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                     "avg_launch_ms": stage_ms["gemm1"]},
+        "stage_ms": stage_ms,
+        "hbm_traffic_gbs": (active * eb + 2 * pf_bytes) / (ms_per_layer * 1e-3) / 1e9,
+    }
+    ctx.close()
+    return out

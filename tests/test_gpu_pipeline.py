@@ -1,0 +1,143 @@
+"""GPU tests of the split-weight prefetch pipeline (paper Section 2 double buffering,
+Section 4.2 multi-buffer grouped GEMM): results must not depend on where an expert lives,
+a layer must never read a staging buffer before its copies have landed, and a staging
+buffer must not be overwritten before its reader is done."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as mo
+from oracle import prefetch_oracle as po
+from paper_2604_01621_amd import inputs
+from tests.util import experts_numpy, to_np, tolerance
+
+pytestmark = pytest.mark.gpu
+
+N_LAYERS, N_RES, N_PEERS = 4, 4, 3
+
+
+@pytest.fixture(scope="module")
+def env(gpu_device):
+    from paper_2604_01621_amd import binding, pipeline
+    cfg = inputs.small_fp8_layer(T=24)
+    ctx = binding.Context(cfg, n_layers=N_LAYERS)
+    layers = pipeline.SplitWeightLayers(ctx, cfg, N_LAYERS, N_RES, N_PEERS, seed=100)
+    xs, lgs, bs = [], [], []
+    for l in range(N_LAYERS):
+        x = inputs.make_activations(cfg, 200 + l)
+        xs.append(x.cuda())
+        lgs.append(inputs.make_gate_logits(cfg, x, 200 + l).cuda())
+        bs.append(inputs.make_bias(cfg, 200 + l, kind="small").cuda())
+    yield binding, pipeline, cfg, ctx, layers, xs, lgs, bs
+    ctx.close()
+
+
+def _reference_outputs(ctx, cfg, layers, xs, lgs, bs):
+    """Every layer computed with a table that reads the peer pool in place (no staging)."""
+    out = []
+    for l in range(N_LAYERS):
+        y = torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device="cuda")
+        ctx.dwdp_moe_forward(l, xs[l], lgs[l], bs[l], layers.all_resident_table(l), y)
+        torch.cuda.synchronize()
+        out.append(y)
+    return out
+
+
+@pytest.mark.parametrize("slice_bytes", [0, 4096, 100000])
+def test_pipeline_poisoned_and_delayed(env, slice_bytes):
+    binding, pipeline, cfg, ctx, layers, xs, lgs, bs = env
+    print("pipeline slice", slice_bytes, flush=True)
+    ref = _reference_outputs(ctx, cfg, layers, xs, lgs, bs)
+    copy_stream = torch.cuda.ExternalStream(ctx.copy_stream_handle())
+    ys = [[torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device="cuda") for _ in range(N_LAYERS)] for _ in range(2)]
+    for b in range(2):
+        layers.poison_staging(b)
+    torch.cuda.synchronize()
+    done = {}
+
+    def poison_then_prefetch(l, it):
+        b = l % 2
+        prev = done.get(b)
+        with torch.cuda.stream(copy_stream):
+            if prev is not None:
+                copy_stream.wait_event(prev)      # the test's own ordering for its poison writes
+            layers.poison_staging(b)
+            torch.cuda._sleep(20_000_000)         # copies arrive late: the layer has to wait for them
+        layers.prefetch(ctx, l, slice_bytes)
+
+    # issue order of the layer-ahead schedule
+    sched = po.pipeline_schedule(N_LAYERS)
+    for it in range(2):
+        for kind, l, b, dep in sched:
+            if kind == "prefetch":
+                poison_then_prefetch(l, it)
+            else:
+                ctx.dwdp_moe_forward(l, xs[l], lgs[l], bs[l], layers.tables[l], ys[it][l])
+                ev = torch.cuda.Event()
+                ev.record(torch.cuda.current_stream())
+                done[b] = ev
+    torch.cuda.synchronize()
+    for it in range(2):
+        for l in range(N_LAYERS):
+            got = ys[it][l].float().cpu().numpy()
+            assert np.isfinite(got).all(), (it, l)
+            np.testing.assert_array_equal(got, ref[l].float().cpu().numpy())
+
+
+def test_pipeline_layers_match_oracle(env):
+    binding, pipeline, cfg, ctx, layers, xs, lgs, bs = env
+    print("pipeline vs oracle", flush=True)
+    ys = [torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device="cuda") for _ in range(N_LAYERS)]
+    for kind, l, b, dep in po.pipeline_schedule(N_LAYERS):
+        if kind == "prefetch":
+            layers.prefetch(ctx, l, 1 << 16)
+        else:
+            ctx.dwdp_moe_forward(l, xs[l], lgs[l], bs[l], layers.tables[l], ys[l])
+    torch.cuda.synchronize()
+    spec = mo.spec_from(cfg)
+    for l in range(N_LAYERS):
+        ref = mo.moe_forward(to_np(xs[l]), to_np(lgs[l]), to_np(bs[l]), experts_numpy(layers.logical[l]), spec)
+        err, l2 = mo.error_metrics(ys[l].float().cpu().numpy(), ref)
+        print(f"  layer {l}: max-rel {err:.3e}", flush=True)
+        assert err <= tolerance(cfg)
+
+
+def test_prefetch_protocol_errors(env):
+    binding, pipeline, cfg, ctx, layers, xs, lgs, bs = env
+    print("pipeline protocol", flush=True)
+    torch.cuda.synchronize()
+    layers.prefetch(ctx, 0, 0)
+    with pytest.raises(binding.DwdpError) as ei:
+        layers.prefetch(ctx, 2, 0)                 # buffer 0 still holds layer 0
+    assert ei.value.status == binding.ESTATE
+    y = torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device="cuda")
+    ctx.dwdp_moe_forward(0, xs[0], lgs[0], bs[0], layers.tables[0], y)     # consumes it
+    layers.prefetch(ctx, 2, 0)
+    ctx.dwdp_moe_forward(2, xs[2], lgs[2], bs[2], layers.tables[2], y)
+    torch.cuda.synchronize()
+    with pytest.raises(binding.DwdpError) as ei:
+        src, dst, nb = layers.prefetch_args(0)
+        ctx.dwdp_prefetch_layer(N_LAYERS, src, dst, nb, N_PEERS, pipeline.N_PARAMS, 0)     # no such layer
+    assert ei.value.status == binding.EINVAL
+
+
+def test_merged_copy_equals_mixed_table(env):
+    """The naive baseline (merge into one contiguous buffer, paper Section 4.2) gives the same bits."""
+    binding, pipeline, cfg, ctx, layers, xs, lgs, bs = env
+    print("merge baseline", flush=True)
+    l = 1
+    layers.prefetch(ctx, l, 0)
+    y_mixed = torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device="cuda")
+    ctx.dwdp_moe_forward(l, xs[l], lgs[l], bs[l], layers.tables[l], y_mixed)
+    torch.cuda.synchronize()
+    n = cfg.n_slots
+    w13 = torch.empty(n, 2 * cfg.I, cfg.H, dtype=torch.uint8, device="cuda")
+    w2 = torch.empty(n, cfg.H, cfg.I, dtype=torch.uint8, device="cuda")
+    s13 = torch.empty(n, 2 * cfg.I // 128, cfg.H // 128, device="cuda")
+    s2 = torch.empty(n, cfg.H // 128, cfg.I // 128, device="cuda")
+    merged = ctx.dwdp_merge_experts(layers.tables[l].cpu().contiguous(), w13, s13, w2, s2)
+    y_merged = torch.empty_like(y_mixed)
+    ctx.dwdp_moe_forward(l, xs[l], lgs[l], bs[l], merged.cuda(), y_merged)
+    torch.cuda.synchronize()
+    assert merged[1, 0] - merged[0, 0] == 2 * cfg.I * cfg.H            # contiguous
+    np.testing.assert_array_equal(y_merged.float().cpu().numpy(), y_mixed.float().cpu().numpy())
