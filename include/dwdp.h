@@ -84,8 +84,8 @@ typedef struct {
  * on the current device.  Allocates the workspace for T_max tokens and a private copy
  * stream at default priority.
  * Supported shapes: H, I multiples of 128; 1 <= K <= E <= 1024; K <= 32; E % n_group == 0;
- * at least 2 experts per group when n_group > 1; K <= topk_group * E / n_group.
- * DWDP_ESHAPE otherwise.
+ * at least 2 experts per group when n_group > 1; K <= topk_group * E / n_group;
+ * T_max * (K + has_shared) * max(H, I) < 2^32 and 2 * I * H < 2^32.  DWDP_ESHAPE otherwise.
  */
 dwdp_status dwdp_create(const dwdp_config* cfg, void* compute_stream, dwdp_ctx** out);
 void dwdp_destroy(dwdp_ctx* ctx);
@@ -146,6 +146,15 @@ dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void* x, const 
  */
 dwdp_status dwdp_prefetch_layer(dwdp_ctx* ctx, int32_t layer, const void* const* src, void* const* dst,
                                 const size_t* bytes, int32_t n_peers, int32_t n_params, size_t slice_bytes);
+
+/*
+ * Kernel selection of the FP8 grouped GEMM.  Experts with 1..max_rows sorted rows are
+ * computed by the weight-streaming kernels (no LDS, one 16-token tile at a time), experts
+ * with more rows by the LDS-tiled kernels (128-token tiles).  Default 16.  0 sends every
+ * expert to the tiled kernels; a value >= T_max sends every expert to the streaming
+ * kernels.  Results are the same function either way (accumulation order differs).
+ */
+dwdp_status dwdp_set_stream_max_rows(dwdp_ctx* ctx, int32_t max_rows);
 
 /*
  * Weight preparation, done once when weights are loaded (on the owner of every expert,

@@ -59,6 +59,7 @@ def _load() -> C.CDLL:
                                          C.POINTER(vp), C.POINTER(vp), C.POINTER(sz), sz, C.POINTER(sz)]
     lib.dwdp_merge_experts.argtypes = [vp, C.POINTER(dwdp_expert_ptrs), i32, vp, vp, vp, vp,
                                        C.POINTER(dwdp_expert_ptrs)]
+    lib.dwdp_set_stream_max_rows.argtypes = [vp, i32]
     lib.dwdp_pack_fp8_weight.argtypes = [vp, vp, vp, C.c_int64, C.c_int64]
     lib.dwdp_profile_enable.argtypes = [vp, i32]
     lib.dwdp_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32)]
@@ -168,6 +169,9 @@ class Context:
         self._check(lib.dwdp_merge_experts(self.h, src, n, _ptr(w13_out), _ptr(s13_out), _ptr(w2_out), _ptr(s2_out),
                                            dst))
         return merged
+
+    def dwdp_set_stream_max_rows(self, max_rows: int):
+        self._check(lib.dwdp_set_stream_max_rows(self.h, max_rows))
 
     def dwdp_pack_fp8_weight(self, src: torch.Tensor, dst: torch.Tensor):
         """src uint8 [..., rows, cols] row-major matrices -> dst (same shape) tile-major, matrix by matrix."""

@@ -22,6 +22,12 @@ struct dwdp_ctx {
   size_t rows_max = 0;
   void* ws[DWDP_N_WS] = {};
   int32_t* chunk_counts = nullptr;
+  // LDS-tiled GEMM schedule (FP8): experts with more than stream_max_rows rows
+  int stream_max_rows = 16;
+  int32_t* mt_expert = nullptr;
+  int32_t* mt_row0 = nullptr;
+  int32_t* n_mtiles = nullptr;
+  int mt_cap = 0;
   // double-buffer protocol
   std::vector<hipEvent_t> staged_ev;  // per layer: its prefetch copies are complete
   hipEvent_t done_ev[2] = {nullptr, nullptr};  // per staging buffer: its last reader finished
@@ -83,6 +89,13 @@ static dwdp_status check_config(const dwdp_config* c) {
   if ((long)c->K > (long)c->topk_group * (c->E / c->n_group))
     return fail(nullptr, DWDP_ESHAPE, "K exceeds the experts of the kept groups");
   if ((long)c->T_max * c->K > (1L << 30)) return fail(nullptr, DWDP_ESHAPE, "T_max * K too large");
+  {
+    // the tiled GEMM addresses activations and one weight matrix with 32-bit byte offsets
+    const long rows = (long)c->T_max * (c->K + c->has_shared);
+    const long wide = c->H > c->I ? c->H : c->I;
+    if (rows * wide >= (1L << 32) || 2L * c->I * c->H >= (1L << 32))
+      return fail(nullptr, DWDP_ESHAPE, "T_max*(K+shared)*max(H,I) and 2*I*H must stay below 2^32");
+  }
   return DWDP_OK;
 }
 
@@ -117,6 +130,10 @@ extern "C" dwdp_status dwdp_create(const dwdp_config* cfg, void* compute_stream,
   const int chunk = permute_chunk_tokens(cfg->E);
   const size_t n_chunks = (T + chunk - 1) / chunk;
   if (e == hipSuccess) e = hipMalloc((void**)&c->chunk_counts, n_chunks * E * 4);
+  c->mt_cap = tile_mtiles_cap((int)c->rows_max, c->n_slots, 0);
+  if (e == hipSuccess) e = hipMalloc((void**)&c->mt_expert, (size_t)c->mt_cap * 4);
+  if (e == hipSuccess) e = hipMalloc((void**)&c->mt_row0, (size_t)c->mt_cap * 4);
+  if (e == hipSuccess) e = hipMalloc((void**)&c->n_mtiles, 4);
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->copy, hipStreamNonBlocking);
   c->staged_ev.assign(cfg->n_layers, nullptr);
   for (int l = 0; l < cfg->n_layers && e == hipSuccess; l++)
@@ -138,6 +155,9 @@ extern "C" void dwdp_destroy(dwdp_ctx* c) {
   for (void* p : c->ws)
     if (p) (void)hipFree(p);
   if (c->chunk_counts) (void)hipFree(c->chunk_counts);
+  if (c->mt_expert) (void)hipFree(c->mt_expert);
+  if (c->mt_row0) (void)hipFree(c->mt_row0);
+  if (c->n_mtiles) (void)hipFree(c->n_mtiles);
   for (hipEvent_t ev : c->staged_ev)
     if (ev) (void)hipEventDestroy(ev);
   for (hipEvent_t ev : c->done_ev)
@@ -245,22 +265,42 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
   if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_QUANT), s));
   GemmArgs ga{table, off, perm, ctx->n_slots, c.E, T, c.H, c.I, c.K};
   const bool fp8 = c.w_dtype == DWDP_W_FP8;
+  // Experts with 1..smr rows stream their weights; the others go through the LDS-tiled kernel.
+  const int rows = T * c.K + (c.has_shared ? T : 0);
+  const int smr = ctx->stream_max_rows;
+  const bool use_tile = fp8 && T > smr;  // an expert holds at most T rows
+  const bool use_stream = smr > 0;
+  TileSched ts{ctx->mt_expert, ctx->mt_row0, ctx->n_mtiles, 0};
   if (fp8) launch_quant_act(x, T, c.H, (uint8_t*)ctx->ws[DWDP_WS_XQ], (float*)ctx->ws[DWDP_WS_XS], s);
+  if (use_tile) {
+    ts.n_mt_max = tile_mtiles_cap(rows, ctx->n_slots, smr);
+    launch_build_mtile_list(off, ctx->n_slots, smr, ts.mt_expert, ts.mt_row0, ts.n_mtiles, ts.n_mt_max, s);
+  }
   // Only the grouped GEMMs read expert weights: the wait for the staged experts goes here.
   if (consume) HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->staged_ev[layer], 0));
   if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM1), s));
   const int span = tl_open(ctx, DWDP_SPAN_GEMM, layer, s);
-  if (fp8)
-    launch_gemm1_fp8(ga, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
-                     (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], s);
-  else
+  if (fp8) {
+    if (use_stream)
+      launch_gemm1_fp8(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
+                       (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], s);
+    if (use_tile)
+      launch_gemm1_fp8_tile(ga, ts, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
+                            (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], s);
+  } else {
     launch_gemm1_bf16(ga, x, ctx->ws[DWDP_WS_HQ], s);
+  }
   if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM2), s));
-  if (fp8)
-    launch_gemm2_fp8(ga, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS], ctx->ws[DWDP_WS_YP],
-                     s);
-  else
+  if (fp8) {
+    if (use_stream)
+      launch_gemm2_fp8(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
+                       ctx->ws[DWDP_WS_YP], s);
+    if (use_tile)
+      launch_gemm2_fp8_tile(ga, ts, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
+                            ctx->ws[DWDP_WS_YP], s);
+  } else {
     launch_gemm2_bf16(ga, ctx->ws[DWDP_WS_HQ], ctx->ws[DWDP_WS_YP], s);
+  }
   tl_close(ctx, span, s);
   // The layer's weights have been read once GEMM-2 is done: release the staging buffer here.
   HIP_TRY(ctx, hipEventRecord(ctx->done_ev[b], s));
@@ -361,6 +401,13 @@ extern "C" dwdp_status dwdp_merge_experts(dwdp_ctx* ctx, const dwdp_expert_ptrs*
     }
     merged_table_host[e] = m;
   }
+  return DWDP_OK;
+}
+
+extern "C" dwdp_status dwdp_set_stream_max_rows(dwdp_ctx* ctx, int32_t max_rows) {
+  if (!ctx) return DWDP_EINVAL;
+  if (max_rows < 0) return fail(ctx, DWDP_EINVAL, "dwdp_set_stream_max_rows: negative");
+  ctx->stream_max_rows = max_rows;
   return DWDP_OK;
 }
 

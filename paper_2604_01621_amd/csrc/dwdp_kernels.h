@@ -46,14 +46,32 @@ struct GemmArgs {
   int n_slots, E, T, H, I, K;
 };
 
+// Device-built list of the M tiles (128 sorted rows of one expert) the LDS-tiled GEMM works on.
+struct TileSched {
+  int32_t* mt_expert;  // [n_mt_max] expert slot of the tile
+  int32_t* mt_row0;    // [n_mt_max] first sorted row
+  int32_t* n_mtiles;   // [1] tiles listed
+  int n_mt_max;        // host-side upper bound used to size the grid
+};
+// Upper bound of listed tiles when experts with more than stream_max_rows rows are listed.
+int tile_mtiles_cap(int rows, int n_slots, int stream_max_rows);
+void launch_build_mtile_list(const int32_t* offsets, int n_slots, int stream_max_rows, int32_t* mt_expert,
+                             int32_t* mt_row0, int32_t* n_mtiles, int cap, hipStream_t stream);
+
 // Row-major fp8 [rows, cols] (rows % 16 == 0, cols % 128 == 0) -> tile-major layout of the FP8 GEMMs.
 void launch_pack_fp8_tiles(const void* src, void* dst, long rows, int cols, hipStream_t stream);
 
 // FP8 (weights tile-major): h = quant(silu(Xq Wg^T) * (Xq Wu^T)); hq fp8 [rows,I], hs fp32 [rows,I/128]
-void launch_gemm1_fp8(const GemmArgs& a, const uint8_t* xq, const float* xs, uint8_t* hq, float* hs,
+// Streaming kernels: experts with 1..max_rows rows.  LDS-tiled kernels: the experts in the tile list.
+void launch_gemm1_fp8(const GemmArgs& a, int max_rows, const uint8_t* xq, const float* xs, uint8_t* hq, float* hs,
                       hipStream_t stream);
+void launch_gemm1_fp8_tile(const GemmArgs& a, const TileSched& ts, const uint8_t* xq, const float* xs, uint8_t* hq,
+                           float* hs, hipStream_t stream);
 // FP8: yp = Hq W2^T, bf16 [rows,H]
-void launch_gemm2_fp8(const GemmArgs& a, const uint8_t* hq, const float* hs, void* yp, hipStream_t stream);
+void launch_gemm2_fp8(const GemmArgs& a, int max_rows, const uint8_t* hq, const float* hs, void* yp,
+                      hipStream_t stream);
+void launch_gemm2_fp8_tile(const GemmArgs& a, const TileSched& ts, const uint8_t* hq, const float* hs, void* yp,
+                           hipStream_t stream);
 // bf16 weights and activations: h fp32 [rows,I]; yp fp32 [rows,H]
 void launch_gemm1_bf16(const GemmArgs& a, const void* x, void* h, hipStream_t stream);
 void launch_gemm2_bf16(const GemmArgs& a, const void* h, void* yp, hipStream_t stream);

@@ -112,14 +112,14 @@ __device__ __forceinline__ void stream_mainloop(const uint8_t* const (&wt)[NT], 
 __global__ __launch_bounds__(kStreamThreads, 2) void gemm1_fp8_stream_kernel(
     const dwdp_expert_ptrs* __restrict__ table, const int32_t* __restrict__ offsets, const int32_t* __restrict__ perm,
     const uint8_t* __restrict__ xq, const float* __restrict__ xs, uint8_t* __restrict__ hq, float* __restrict__ hs,
-    int E, int T, int H, int I, int K) {
+    int E, int T, int H, int I, int K, int max_rows) {
   __shared__ float amax_s[4][16];
   const int njb = I / 128;
   const int e = blockIdx.x / njb;
   const int jb = blockIdx.x - e * njb;
   const int r0 = offsets[e];
   const int r1 = offsets[e + 1];
-  if (r1 <= r0) return;  // expert without tokens: its weights are never touched
+  if (r1 <= r0 || r1 - r0 > max_rows) return;  // no tokens: weights never touched; many: tiled kernel
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 15, lq = lane >> 4;
   const int nkb = H / 128;
   const uint8_t* w13 = (const uint8_t*)table[e].w13;
@@ -175,13 +175,13 @@ __global__ __launch_bounds__(kStreamThreads, 2) void gemm1_fp8_stream_kernel(
 // Task = (expert slot e, block nb of 128 output rows).  Wave w owns rows nb*128 + w*32 + {0..31}.
 __global__ __launch_bounds__(kStreamThreads, 2) void gemm2_fp8_stream_kernel(
     const dwdp_expert_ptrs* __restrict__ table, const int32_t* __restrict__ offsets, const uint8_t* __restrict__ hq,
-    const float* __restrict__ hs, uint16_t* __restrict__ yp, int H, int I) {
+    const float* __restrict__ hs, uint16_t* __restrict__ yp, int H, int I, int max_rows) {
   const int nnb = H / 128;
   const int e = blockIdx.x / nnb;
   const int nb = blockIdx.x - e * nnb;
   const int r0 = offsets[e];
   const int r1 = offsets[e + 1];
-  if (r1 <= r0) return;
+  if (r1 <= r0 || r1 - r0 > max_rows) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 15, lq = lane >> 4;
   const int nkb = I / 128;
   const uint8_t* w2 = (const uint8_t*)table[e].w2;
@@ -213,19 +213,20 @@ __global__ __launch_bounds__(kStreamThreads, 2) void gemm2_fp8_stream_kernel(
   }
 }
 
-void launch_gemm1_fp8(const GemmArgs& a, const uint8_t* xq, const float* xs, uint8_t* hq, float* hs,
+void launch_gemm1_fp8(const GemmArgs& a, int max_rows, const uint8_t* xq, const float* xs, uint8_t* hq, float* hs,
                       hipStream_t stream) {
   if (a.T <= 0) return;
   dim3 grid(a.n_slots * (a.I / 128));
   hipLaunchKernelGGL(gemm1_fp8_stream_kernel, grid, dim3(kStreamThreads), 0, stream, a.table, a.offsets, a.perm, xq,
-                     xs, hq, hs, a.E, a.T, a.H, a.I, a.K);
+                     xs, hq, hs, a.E, a.T, a.H, a.I, a.K, max_rows);
 }
 
-void launch_gemm2_fp8(const GemmArgs& a, const uint8_t* hq, const float* hs, void* yp, hipStream_t stream) {
+void launch_gemm2_fp8(const GemmArgs& a, int max_rows, const uint8_t* hq, const float* hs, void* yp,
+                      hipStream_t stream) {
   if (a.T <= 0) return;
   dim3 grid(a.n_slots * (a.H / 128));
   hipLaunchKernelGGL(gemm2_fp8_stream_kernel, grid, dim3(kStreamThreads), 0, stream, a.table, a.offsets, hq, hs,
-                     (uint16_t*)yp, a.H, a.I);
+                     (uint16_t*)yp, a.H, a.I, max_rows);
 }
 
 // Row-major fp8 [rows, cols] -> tile-major.  Tile (tr, kb) = rows tr*16.., columns kb*128..

@@ -130,11 +130,13 @@ def test_pack_fp8_weight_layout(binding):
     ctx.close()
 
 
-def _layer_case(binding, cfg, x, logits, bias, w, check_intermediates=False):
+def _layer_case(binding, cfg, x, logits, bias, w, check_intermediates=False, stream_max_rows=None):
     dev = "cuda"
     wd = inputs.ExpertWeights(w.w13.to(dev), w.w2.to(dev), None if w.s13 is None else w.s13.to(dev),
                               None if w.s2 is None else w.s2.to(dev))
     ctx = binding.Context(cfg)
+    if stream_max_rows is not None:
+        ctx.dwdp_set_stream_max_rows(stream_max_rows)
     table = binding.expert_table(ctx.pack_experts(wd))
     xd, ld = x.to(dev), logits.to(dev)
     bd = None if bias is None else bias.to(dev)
@@ -174,28 +176,32 @@ def test_layer_tiny_bf16(binding, seed):
     _layer_case(binding, cfg, x, logits, bias, w, check_intermediates=True)
 
 
+@pytest.mark.parametrize("smr", [0, 16, 1 << 30])
 @pytest.mark.parametrize("T", [1, 7, 48, 333])
-def test_layer_small_fp8(binding, T):
+def test_layer_small_fp8(binding, T, smr):
     """Scaled-down sigmoid/group-limited FP8 layer: several 16-token tiles with a ragged tail,
-    experts without tokens, shared expert."""
-    print("layer small fp8 T", T, flush=True)
+    experts without tokens, shared expert.  smr selects the kernels: 0 = LDS-tiled for every
+    expert, 16 = the default split, 2^30 = weight-streaming for every expert."""
+    print("layer small fp8 T", T, "stream_max_rows", smr, flush=True)
     cfg = inputs.small_fp8_layer(T=T)
     x = inputs.make_activations(cfg, T)
     logits = inputs.make_gate_logits(cfg, x, T)
     bias = inputs.make_bias(cfg, T, kind="small")
     w = inputs.make_expert_weights(cfg, T)
-    _layer_case(binding, cfg, x, logits, bias, w, check_intermediates=True)
+    _layer_case(binding, cfg, x, logits, bias, w, check_intermediates=True, stream_max_rows=smr)
 
 
-@pytest.mark.parametrize("H,I,T", [(1536, 1024, 37), (1408, 640, 20)])
-def test_layer_fp8_long_k(binding, H, I, T):
-    """K loops of several pipeline rounds plus a remainder (H/128 = 12 or 11, I/128 = 8 or 5)."""
-    print("layer fp8 long-k", H, I, T, flush=True)
+@pytest.mark.parametrize("smr", [0, 1 << 30])
+@pytest.mark.parametrize("H,I,T", [(1536, 1024, 37), (1408, 640, 20), (640, 384, 300)])
+def test_layer_fp8_long_k(binding, H, I, T, smr):
+    """K loops of several pipeline rounds plus a remainder (H/128 = 12, 11 or 5; I/128 = 8, 5
+    or 3), output rows not a multiple of the 256-row workgroup tile, on both kernel families."""
+    print("layer fp8 long-k", H, I, T, smr, flush=True)
     cfg = inputs.small_fp8_layer(T=T, H=H, I=I, E=8, K=2, n_group=1, topk_group=1)
     x = inputs.make_activations(cfg, 21)
     logits = inputs.make_gate_logits(cfg, x, 21)
     w = inputs.make_expert_weights(cfg, 21)
-    _layer_case(binding, cfg, x, logits, None, w, check_intermediates=True)
+    _layer_case(binding, cfg, x, logits, None, w, check_intermediates=True, stream_max_rows=smr)
 
 
 def test_layer_small_fp8_no_shared_and_empty(binding):
