@@ -46,7 +46,7 @@ struct GemmArgs {
   int n_slots, E, T, H, I, K;
 };
 
-// Device-built list of the M tiles (128 sorted rows of one expert) the LDS-tiled GEMM works on.
+// Device-built list of the M tiles (up to 320 sorted rows of one expert) the LDS-tiled GEMM works on.
 struct TileSched {
   int32_t* mt_expert;  // [n_mt_max] expert slot of the tile
   int32_t* mt_row0;    // [n_mt_max] first sorted row

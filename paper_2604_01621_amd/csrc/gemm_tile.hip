@@ -1,18 +1,23 @@
 // LDS-tiled FP8 grouped GEMM for gfx950: the large-M (prefill-shaped) path.
 //
-// A workgroup (4 waves) computes a 256 (weight rows) x 128 (tokens) output tile of one
-// expert.  Per 128-wide K block -- exactly one weight-scale block and one activation-scale
-// group -- it stages 16 packed weight tiles (32 KiB, contiguous 2 KiB pieces located
-// through the expert-pointer table) and 8 packed token tiles (16 KiB, rows gathered through
-// the permutation) in LDS; each wave then runs 4 x 8 v_mfma_f32_16x16x128_f8f6f4 and folds
-// every fp32 partial product into its accumulator with s_act[token,kb] * s_w[nblock,kb] on
-// the VALU.  Global loads for K block kb+1 are in flight in registers while block kb is
-// multiplied (two workgroups per CU hide the barriers of one another).
+// A workgroup of 8 waves computes a 256 (weight rows) x 288 (tokens) output tile of one
+// expert.  288 tokens cover almost every expert of the prefill workload (256 +- 16 rows), so
+// each weight panel is read from HBM once; with 128-token tiles the panels were re-read by
+// every M tile and the kernel ran at HBM speed.  Per 128-wide K block -- exactly one
+// weight-scale block and one activation-scale group -- the workgroup stages 16 packed
+// weight tiles (32 KiB, contiguous 2 KiB pieces located through the expert-pointer table)
+// and up to 18 packed token tiles (36 KiB, rows gathered through the permutation) in LDS;
+// wave (wn, wm) multiplies weight tiles 4*wn..4*wn+3 with token tiles wm, wm+2, ... on
+// v_mfma_f32_16x16x128_f8f6f4 and folds every fp32 partial product into its accumulator
+// with s_act[token,kb] * s_w[nblock,kb] on the VALU.  The LDS image of K block kb+1 is
+// filled by asynchronous global->LDS copies (global_load_lds_dwordx4, no staging registers,
+// no ds_write) while block kb is multiplied; two images of 68 KiB alternate, one barrier
+// per K block.
 //
-// Token tiles of 16 beyond the expert's row count are skipped, so padding costs LDS
-// traffic only.  Workgroups are numbered so that all M tiles of one (expert, weight panel)
-// run on the same XCD at about the same time and share its L2: block b runs on XCD b % 8
-// and handles panel x + 8*jj, M tile m with b / 8 = jj * n_mt_max + m.
+// Token tiles of 16 beyond the expert's row count are skipped (not loaded, not
+// multiplied).  Workgroups are numbered so that all weight panels of one M tile run on the
+// same XCD back to back and share the token rows in its L2: block b runs on XCD b % 8 and
+// handles M tile (b/8 / n_panels) * 8 + b % 8, panel (b/8) % n_panels.
 //
 // GEMM-1 (G1): rows = 128 gate + 128 up rows of W13, epilogue silu(g)*u, per-token amax
 // over the block's 128 h columns, e4m3 quantisation of h.  GEMM-2: rows = 256 rows of W2,
@@ -21,13 +26,20 @@
 
 namespace dwdp {
 
-constexpr int kBM = 128;          // tokens per workgroup tile
-constexpr int kTT = kBM / 16;     // token tiles per workgroup
-constexpr int kTileThreads = 256;
+constexpr int kBM = 288;          // tokens per workgroup tile
+constexpr int kTT = kBM / 16;     // token tiles per workgroup (18)
+constexpr int kTW = kTT / 2;      // token tiles per wave (9)
+constexpr int kTileThreads = 512;
+constexpr int kLdsA = 16 * kTileBytes;
+constexpr int kLdsB = kTT * kTileBytes;
+constexpr int kSaLen = 320;
+static_assert(kBM <= kSaLen && kTT <= 20 && kTT % 2 == 0, "copy loops cover 40 token half-tiles and 320 scales");
 
 typedef const __attribute__((address_space(1))) v4i* gv4i;
 typedef const __attribute__((address_space(1))) float* gf32;
-typedef __attribute__((address_space(3))) v4i* lv4i;
+// Read-only data addressed with wave-uniform pointers: the constant address space makes
+// these scalar loads (s_load), which do not touch the vector-memory counter the copies use.
+typedef const __attribute__((address_space(4))) float* cf32;
 
 __device__ __forceinline__ v8i cat8(v4i lo, v4i hi) { return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7); }
 
@@ -55,63 +67,82 @@ __global__ __launch_bounds__(1024) void build_mtile_list_kernel(const int32_t* _
   }
 }
 
+typedef __attribute__((address_space(1))) const void* gvoid;
+typedef __attribute__((address_space(3))) void* lvoid;
+
+// Asynchronous global -> LDS copy of 64 lanes x 16 bytes: lane l's 16 bytes land at dst + l*16.
+__device__ __forceinline__ void dma16(const uint8_t* src_lane, uint8_t* dst_wave_uniform) {
+  __builtin_amdgcn_global_load_lds((gvoid)src_lane, (lvoid)dst_wave_uniform, 16, 0, 0);
+}
+__device__ __forceinline__ void dma4(const float* src_lane, float* dst_wave_uniform) {
+  __builtin_amdgcn_global_load_lds((gvoid)src_lane, (lvoid)dst_wave_uniform, 4, 0, 0);
+}
+
 template <bool G1>
-__global__ __launch_bounds__(kTileThreads, 2) void gemm_fp8_tile_kernel(
+__global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
     const dwdp_expert_ptrs* __restrict__ table, const int32_t* __restrict__ offsets, const int32_t* __restrict__ perm,
     const int32_t* __restrict__ mt_expert, const int32_t* __restrict__ mt_row0, const int32_t* __restrict__ n_mtiles,
-    int n_mt_max, int n_panels, const uint8_t* __restrict__ act, const float* __restrict__ act_s,
-    uint8_t* __restrict__ hq, float* __restrict__ hs, uint16_t* __restrict__ yp, int E, int T, int H, int I, int K) {
-  __shared__ __attribute__((aligned(16))) uint8_t lds_a[16 * kTileBytes];
-  __shared__ __attribute__((aligned(16))) uint8_t lds_b[kTT * kTileBytes];
-  __shared__ float lds_sa[kBM];
-  __shared__ float lds_amax[4][kBM];
+    int n_panels, const uint8_t* __restrict__ act, const float* __restrict__ act_s, uint8_t* __restrict__ hq,
+    float* __restrict__ hs, uint16_t* __restrict__ yp, int E, int T, int H, int I, int K) {
+  // Two LDS images (K block kb and kb+1), each its own array so that the compiler can tell
+  // a copy into one from the reads of the other.
+  __shared__ __attribute__((aligned(16))) uint8_t lds_a0[kLdsA];
+  __shared__ __attribute__((aligned(16))) uint8_t lds_a1[kLdsA];
+  __shared__ __attribute__((aligned(16))) uint8_t lds_b0[kLdsB];
+  __shared__ __attribute__((aligned(16))) uint8_t lds_b1[kLdsB];
+  __shared__ __attribute__((aligned(16))) float lds_sa0[kSaLen];  // 5 waves x 64 activation scales
+  __shared__ __attribute__((aligned(16))) float lds_sa1[kSaLen];
+  __shared__ float lds_amax[4 * kBM];
 
   const int xcd = blockIdx.x & 7;
   const int s = blockIdx.x >> 3;
-  const int jj = s / n_mt_max;
-  const int m = s - jj * n_mt_max;
-  const int panel = xcd + 8 * jj;
-  if (panel >= n_panels || m >= *n_mtiles) return;
-  const int e = mt_expert[m];
-  const int r0 = mt_row0[m];
-  const int r_end = offsets[e + 1];
+  const int mq = s / n_panels;
+  const int panel = s - mq * n_panels;
+  const int m = mq * 8 + xcd;
+  if (m >= *n_mtiles) return;
+  // wave-uniform values go through readfirstlane so that everything derived from them
+  // (weight/scale pointers, tile counts) lives in scalar registers and is loaded with s_load
+  const int e = __builtin_amdgcn_readfirstlane(mt_expert[m]);
+  const int r0 = __builtin_amdgcn_readfirstlane(mt_row0[m]);
+  const int r_end = __builtin_amdgcn_readfirstlane(offsets[e + 1]);
   const int valid = min(kBM, r_end - r0);
   const int ntt = (valid + 15) >> 4;
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63, lr = lane & 15, lq = lane >> 4;
-  const int Kdim = G1 ? H : I;           // reduction length
+  const int wn = wave & 3, wm = wave >> 2;
+  const int Kdim = G1 ? H : I;  // reduction length
   const int nkb = Kdim / 128;
   const int n_tile_rows = (G1 ? 2 * I : H) / 16;
   const uint8_t* wbase = (const uint8_t*)(G1 ? table[e].w13 : table[e].w2);
   const float* sbase = G1 ? table[e].s13 : table[e].s2;
 
-  // ---- loader addresses (fixed over the K loop) ----
-  const int within = tid & 127;
-  uint32_t a_src[8];  // byte offsets from wbase / act: 32-bit to keep the loop's address registers few
+  // ---- copy sources (fixed over the K loop) ----
+  // weights: wave w copies LDS tiles 2w and 2w+1 (4 pieces of 1 KiB); LDS tile a = wn*4 + j
+  const uint8_t* a_src[2];
 #pragma unroll
-  for (int i = 0; i < 8; i++) {
-    const int a = (tid >> 7) + 2 * i;  // LDS tile 0..15 = wave*4 + j
+  for (int i = 0; i < 2; i++) {
+    const int a = wave * 2 + i;
     const int w = a >> 2, j = a & 3;
     int tr;
     if (G1)
       tr = (j < 2 ? 0 : I / 16) + panel * 8 + 2 * w + (j & 1);
     else
       tr = min(panel * 16 + a, n_tile_rows - 1);
-    a_src[i] = (uint32_t)tr * nkb * kTileBytes + within * 16;
+    a_src[i] = wbase + (size_t)tr * nkb * kTileBytes + lane * 16;
   }
-  uint32_t b_src[4];
+  // tokens: wave w copies 1 KiB pieces c = w, w+8, ... (piece c = token tile c/2, half c&1)
+  uint32_t b_src[5];
 #pragma unroll
-  for (int i = 0; i < 4; i++) {
-    const int tt = (tid >> 7) + 2 * i;
-    const int half = within >> 6, l = within & 63;
-    const int row = min(r0 + tt * 16 + (l & 15), r_end - 1);
+  for (int i = 0; i < 5; i++) {
+    const int c = wave + 8 * i;
+    const int row = min(r0 + (c >> 1) * 16 + lr, r_end - 1);
     const int src_row = G1 ? ((e < E) ? perm[row] / K : row - T * K) : row;
-    b_src[i] = (uint32_t)src_row * Kdim + (l >> 4) * 32 + half * 16;
+    b_src[i] = (uint32_t)src_row * Kdim + lq * 32 + (c & 1) * 16;
   }
   const float* sa_src;
   {
-    const int row = min(r0 + (tid & 127), r_end - 1);
+    const int row = min(r0 + min(wave, 4) * 64 + lane, r_end - 1);
     const int src_row = G1 ? ((e < E) ? perm[row] / K : row - T * K) : row;
     sa_src = act_s + (size_t)src_row * nkb;
   }
@@ -122,55 +153,47 @@ __global__ __launch_bounds__(kTileThreads, 2) void gemm_fp8_tile_kernel(
     sw0 = sbase + (size_t)panel * nkb;
     sw1 = sbase + (size_t)(I / 128 + panel) * nkb;
   } else {
-    const int blk = min(panel * 2 + (wave >> 1), H / 128 - 1);
+    const int blk = min(panel * 2 + (wn >> 1), H / 128 - 1);
     sw0 = sw1 = sbase + (size_t)blk * nkb;
   }
 
-  v4f acc[4][kTT];
+  v4f acc[4][kTW];
 #pragma unroll
   for (int j = 0; j < 4; j++)
 #pragma unroll
-    for (int t = 0; t < kTT; t++) acc[j][t] = (v4f){0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < kTW; t++) acc[j][t] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-  v4i ra[8], rb[4];
-  float rsa;
+  auto issue = [&](uint8_t* la, uint8_t* lb, float* lsa, int kb) {
 #pragma unroll
-  for (int i = 0; i < 8; i++) ra[i] = __builtin_nontemporal_load((gv4i)(wbase + a_src[i]));
-#pragma unroll
-  for (int i = 0; i < 4; i++) rb[i] = *(gv4i)(act + b_src[i]);
-  rsa = *(gf32)sa_src;
-
-  for (int kb = 0; kb < nkb; kb++) {
-    // registers -> LDS
-#pragma unroll
-    for (int i = 0; i < 8; i++) *(v4i*)(lds_a + ((tid >> 7) + 2 * i) * kTileBytes + within * 16) = ra[i];
-#pragma unroll
-    for (int i = 0; i < 4; i++) *(v4i*)(lds_b + ((tid >> 7) + 2 * i) * kTileBytes + within * 16) = rb[i];
-    if (tid < kBM) lds_sa[tid] = rsa;
-    __syncthreads();
-    // next K block's global loads fly during the MFMAs (the last round re-reads block nkb-1)
-    {
-      const int kn = min(kb + 1, nkb - 1);
-#pragma unroll
-      for (int i = 0; i < 8; i++) ra[i] = __builtin_nontemporal_load((gv4i)(wbase + (a_src[i] + (uint32_t)kn * kTileBytes)));
-#pragma unroll
-      for (int i = 0; i < 4; i++) rb[i] = *(gv4i)(act + (b_src[i] + (uint32_t)kn * 128));
-      rsa = *(gf32)(sa_src + kn);
+    for (int i = 0; i < 2; i++) {
+      const uint8_t* p = a_src[i] + (size_t)kb * kTileBytes;
+      dma16(p, la + (wave * 2 + i) * kTileBytes);
+      dma16(p + kTileBytes / 2, la + (wave * 2 + i) * kTileBytes + kTileBytes / 2);
     }
-    const float w0 = *(gf32)(sw0 + kb);
-    const float w1 = *(gf32)(sw1 + kb);
+#pragma unroll
+    for (int i = 0; i < 5; i++) {
+      const int c = wave + 8 * i;
+      if (c < 2 * ntt) dma16(act + (b_src[i] + (uint32_t)kb * 128), lb + c * (kTileBytes / 2));
+    }
+    if (wave < 5) dma4(sa_src + kb, lsa + wave * 64);
+  };
+
+  auto compute = [&](const uint8_t* la, const uint8_t* lb, const float* lsa, int kb) {
+    const float w0 = *(cf32)(sw0 + kb);
+    const float w1 = *(cf32)(sw1 + kb);
     v8i af[4];
 #pragma unroll
     for (int j = 0; j < 4; j++) {
-      const uint8_t* p = lds_a + (wave * 4 + j) * kTileBytes + lane * 16;
+      const uint8_t* p = la + (wn * 4 + j) * kTileBytes + lane * 16;
       af[j] = cat8(*(const v4i*)p, *(const v4i*)(p + kTileBytes / 2));
     }
 #pragma unroll
-    for (int t = 0; t < kTT; t++) {
+    for (int ti = 0; ti < kTW; ti++) {
+      const int t = wm + 2 * ti;
       if (t < ntt) {
-        const uint8_t* p = lds_b + t * kTileBytes + lane * 16;
+        const uint8_t* p = lb + t * kTileBytes + lane * 16;
         const v8i bf = cat8(*(const v4i*)p, *(const v4i*)(p + kTileBytes / 2));
-        const float sa = lds_sa[t * 16 + lr];
+        const float sa = lsa[t * 16 + lr];
         const float s0 = sa * w0, s1 = sa * w1;
 #pragma unroll
         for (int j = 0; j < 4; j++) {
@@ -178,66 +201,82 @@ __global__ __launch_bounds__(kTileThreads, 2) void gemm_fp8_tile_kernel(
           const v4f pr = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af[j], bf, zero, 0, 0, 0, 0, 0, 0);
           const float sj = (j < 2) ? s0 : s1;
 #pragma unroll
-          for (int i = 0; i < 4; i++) acc[j][t][i] = fmaf(pr[i], sj, acc[j][t][i]);
+          for (int i = 0; i < 4; i++) acc[j][ti][i] = fmaf(pr[i], sj, acc[j][ti][i]);
         }
       }
     }
-    __syncthreads();  // everyone is done with this K block's LDS image
+  };
+
+  // One barrier per K block: it publishes the image copied during the previous block and
+  // retires the reads of the image that the next copy overwrites.
+  issue(lds_a0, lds_b0, lds_sa0, 0);
+  for (int kb = 0; kb < nkb; kb += 2) {
+    __syncthreads();
+    if (kb + 1 < nkb) issue(lds_a1, lds_b1, lds_sa1, kb + 1);
+    compute(lds_a0, lds_b0, lds_sa0, kb);
+    if (kb + 1 < nkb) {
+      __syncthreads();
+      if (kb + 2 < nkb) issue(lds_a0, lds_b0, lds_sa0, kb + 2);
+      compute(lds_a1, lds_b1, lds_sa1, kb + 1);
+    }
   }
 
   if (G1) {
     const int njb = I / 128;
     // h = silu(gate) * up, kept in acc[0..1]
 #pragma unroll
-    for (int t = 0; t < kTT; t++) {
+    for (int ti = 0; ti < kTW; ti++) {
+      const int t = wm + 2 * ti;
       float amax = 0.f;
       if (t < ntt) {
 #pragma unroll
         for (int j = 0; j < 2; j++)
 #pragma unroll
           for (int i = 0; i < 4; i++) {
-            const float g = acc[j][t][i], u = acc[2 + j][t][i];
+            const float g = acc[j][ti][i], u = acc[2 + j][ti][i];
             const float v = g / (1.f + __expf(-g)) * u;
-            acc[j][t][i] = v;
+            acc[j][ti][i] = v;
             amax = fmaxf(amax, fabsf(v));
           }
       }
       amax = fmaxf(amax, __shfl_xor(amax, 16));
       amax = fmaxf(amax, __shfl_xor(amax, 32));
-      if (lq == 0) lds_amax[wave][t * 16 + lr] = amax;
+      if (lq == 0) lds_amax[wn * kBM + t * 16 + lr] = amax;
     }
     __syncthreads();
 #pragma unroll
-    for (int t = 0; t < kTT; t++) {
+    for (int ti = 0; ti < kTW; ti++) {
+      const int t = wm + 2 * ti;
       if (t < ntt) {
         const int tok = t * 16 + lr;
-        const float amax =
-            fmaxf(fmaxf(lds_amax[0][tok], lds_amax[1][tok]), fmaxf(lds_amax[2][tok], lds_amax[3][tok]));
+        const float amax = fmaxf(fmaxf(lds_amax[tok], lds_amax[kBM + tok]),
+                                 fmaxf(lds_amax[2 * kBM + tok], lds_amax[3 * kBM + tok]));
         const float scale = amax > 0.f ? amax / 448.f : 1.f;
         const int r = r0 + tok;
         if (r < r_end) {
 #pragma unroll
           for (int j = 0; j < 2; j++) {
-            const uint32_t q = pack_fp8x4(acc[j][t][0] / scale, acc[j][t][1] / scale, acc[j][t][2] / scale,
-                                          acc[j][t][3] / scale);
-            *(uint32_t*)(hq + (size_t)r * I + panel * 128 + wave * 32 + j * 16 + lq * 4) = q;
+            const uint32_t q = pack_fp8x4(acc[j][ti][0] / scale, acc[j][ti][1] / scale, acc[j][ti][2] / scale,
+                                          acc[j][ti][3] / scale);
+            *(uint32_t*)(hq + (size_t)r * I + panel * 128 + wn * 32 + j * 16 + lq * 4) = q;
           }
-          if (wave == 0 && lq == 0) hs[(size_t)r * njb + panel] = scale;
+          if (wn == 0 && lq == 0) hs[(size_t)r * njb + panel] = scale;
         }
       }
     }
   } else {
 #pragma unroll
     for (int j = 0; j < 4; j++) {
-      const int n0 = panel * 256 + (wave * 4 + j) * 16;
+      const int n0 = panel * 256 + (wn * 4 + j) * 16;
       if (n0 < H) {
 #pragma unroll
-        for (int t = 0; t < kTT; t++) {
+        for (int ti = 0; ti < kTW; ti++) {
+          const int t = wm + 2 * ti;
           const int r = r0 + t * 16 + lr;
           if (t < ntt && r < r_end) {
             uint2 o;
-            o.x = (uint32_t)f32_to_bf16(acc[j][t][0]) | ((uint32_t)f32_to_bf16(acc[j][t][1]) << 16);
-            o.y = (uint32_t)f32_to_bf16(acc[j][t][2]) | ((uint32_t)f32_to_bf16(acc[j][t][3]) << 16);
+            o.x = (uint32_t)f32_to_bf16(acc[j][ti][0]) | ((uint32_t)f32_to_bf16(acc[j][ti][1]) << 16);
+            o.y = (uint32_t)f32_to_bf16(acc[j][ti][2]) | ((uint32_t)f32_to_bf16(acc[j][ti][3]) << 16);
             *(uint2*)(yp + (size_t)r * H + n0 + lq * 4) = o;
           }
         }
@@ -262,18 +301,18 @@ void launch_build_mtile_list(const int32_t* offsets, int n_slots, int stream_max
 void launch_gemm1_fp8_tile(const GemmArgs& a, const TileSched& ts, const uint8_t* xq, const float* xs, uint8_t* hq,
                            float* hs, hipStream_t stream) {
   const int n_panels = a.I / 128;
-  const int grid = 8 * ((n_panels + 7) / 8) * ts.n_mt_max;
-  hipLaunchKernelGGL(gemm_fp8_tile_kernel<true>, dim3(grid), dim3(kTileThreads), 0, stream, a.table, a.offsets, a.perm,
-                     ts.mt_expert, ts.mt_row0, ts.n_mtiles, ts.n_mt_max, n_panels, xq, xs, hq, hs, (uint16_t*)nullptr,
-                     a.E, a.T, a.H, a.I, a.K);
+  const int grid = 8 * ((ts.n_mt_max + 7) / 8) * n_panels;
+  hipLaunchKernelGGL(gemm_fp8_tile_kernel<true>, dim3(grid), dim3(kTileThreads), 0, stream, a.table,
+                     a.offsets, a.perm, ts.mt_expert, ts.mt_row0, ts.n_mtiles, n_panels, xq, xs, hq, hs,
+                     (uint16_t*)nullptr, a.E, a.T, a.H, a.I, a.K);
 }
 
 void launch_gemm2_fp8_tile(const GemmArgs& a, const TileSched& ts, const uint8_t* hq, const float* hs, void* yp,
                            hipStream_t stream) {
   const int n_panels = (a.H + 255) / 256;
-  const int grid = 8 * ((n_panels + 7) / 8) * ts.n_mt_max;
-  hipLaunchKernelGGL(gemm_fp8_tile_kernel<false>, dim3(grid), dim3(kTileThreads), 0, stream, a.table, a.offsets,
-                     a.perm, ts.mt_expert, ts.mt_row0, ts.n_mtiles, ts.n_mt_max, n_panels, hq, hs, (uint8_t*)nullptr,
+  const int grid = 8 * ((ts.n_mt_max + 7) / 8) * n_panels;
+  hipLaunchKernelGGL(gemm_fp8_tile_kernel<false>, dim3(grid), dim3(kTileThreads), 0, stream, a.table,
+                     a.offsets, a.perm, ts.mt_expert, ts.mt_row0, ts.n_mtiles, n_panels, hq, hs, (uint8_t*)nullptr,
                      (float*)nullptr, (uint16_t*)yp, a.E, a.T, a.H, a.I, a.K);
 }
 
