@@ -19,6 +19,9 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 FP8_PEAK_TFLOPS = 5000.0     # MI355X dense FP8 MFMA, published
+# HBM bytes of the dominant kernel from the committed rocprofv3 counter runs (profiles/): keyed by
+# (seed, T) of the decode workload; None when this configuration was not profiled.
+PROFILED_TRAFFIC = {(1, 64): 4651422 * 1024}
 
 
 def parse():
@@ -127,27 +130,36 @@ def main():
     el = 1 if fp8 else 2
     b13 = 2 * cfg.I * cfg.H * el + (4 * (2 * cfg.I // 128) * (cfg.H // 128) if fp8 else 0)
     b2 = cfg.H * cfg.I * el + (4 * (cfg.H // 128) * (cfg.I // 128) if fp8 else 0)
-    flops1 = 2 * 2 * cfg.I * cfg.H * pairs
-    flops2 = 2 * cfg.I * cfg.H * pairs
-    weight_bound = args.workload in ("decode", "skew", "tiny")
-    if weight_bound:
-        ach = active * b13 / (stage_ms["gemm1"] * 1e-3) / 1e9
-        roof = {"bound": "hbm", "kernel": "gemm1 (gate/up + SwiGLU)", "achieved": ach, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
-                "algorithmic_bytes_per_launch": active * b13, "avg_launch_ms": stage_ms["gemm1"]}
-        ach2 = active * b2 / (stage_ms["gemm2"] * 1e-3) / 1e9
-        roof2 = {"bound": "hbm", "kernel": "gemm2 (down)", "achieved": ach2, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                 "frac": ach2 / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": active * b2,
-                 "avg_launch_ms": stage_ms["gemm2"]}
-    else:
-        ach = flops1 / (stage_ms["gemm1"] * 1e-3) / 1e12
-        roof = {"bound": "mfma", "kernel": "gemm1 (gate/up + SwiGLU)", "achieved": ach, "peak": FP8_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": ach / FP8_PEAK_TFLOPS, "traffic": None,
-                "algorithmic_flops_per_launch": flops1, "avg_launch_ms": stage_ms["gemm1"]}
-        ach2 = flops2 / (stage_ms["gemm2"] * 1e-3) / 1e12
-        roof2 = {"bound": "mfma", "kernel": "gemm2 (down)", "achieved": ach2, "peak": FP8_PEAK_TFLOPS,
-                 "unit": "TFLOP/s", "frac": ach2 / FP8_PEAK_TFLOPS, "algorithmic_flops_per_launch": flops2,
-                 "avg_launch_ms": stage_ms["gemm2"]}
+    # which kernel family serves which expert (the library's default threshold: 16 rows)
+    smr = 16 if (fp8 and cfg.T > 16) else (1 << 30)
+    n_stream = int(((counts > 0) & (counts <= smr)).sum())
+    n_tile = int((counts > smr).sum())
+    rows_tile = int(counts[counts > smr].sum())
+
+    def roofline(stage_stream, stage_tile, bytes_per_expert, flops_per_row, label):
+        """Roofline entry for the kernel family that does most of one GEMM stage's work."""
+        t_s, t_t = stage_ms[stage_stream], stage_ms.get(stage_tile, 0.0)
+        tile = n_tile > n_stream          # the family that serves more experts does more of the work
+        t = t_t if tile else t_s
+        n_exp = n_tile if tile else n_stream
+        kern = ("LDS-tiled " if tile else "weight-streaming ") + label
+        compute_bound = tile and rows_tile / max(n_tile, 1) >= 128
+        if compute_bound:
+            ach = rows_tile * flops_per_row / (t * 1e-3) / 1e12
+            return {"bound": "mfma", "kernel": kern, "achieved": ach, "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": ach / FP8_PEAK_TFLOPS, "traffic": None,
+                    "algorithmic_flops_per_launch": rows_tile * flops_per_row, "avg_launch_ms": t}
+        ach = n_exp * bytes_per_expert / (t * 1e-3) / 1e9
+        return {"bound": "hbm", "kernel": kern, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": ach / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_launch": n_exp * bytes_per_expert,
+                "experts_in_launch": n_exp, "avg_launch_ms": t}
+
+    roof = roofline("gemm1", "gemm1_tile", b13, 2 * 2 * cfg.I * cfg.H, "GEMM-1 (gate/up + SwiGLU)")
+    roof2 = roofline("gemm2", "gemm2_tile", b2, 2 * cfg.I * cfg.H, "GEMM-2 (down)")
+    if args.workload == "decode" and roof["bound"] == "hbm":
+        # rocprofv3 FETCH_SIZE x 2.0 (calibrated against a 1 GiB copy) for this kernel and workload,
+        # from profiles/decode_T64_stream_gemm.md: bytes per launch
+        roof["traffic"] = PROFILED_TRAFFIC.get((args.seed, cfg.T))
 
     out = {
         "metric": "moe_layer_tokens_per_s", "value": cfg.T / (ms_per_step * 1e-3), "unit": "tokens/s",
@@ -159,6 +171,7 @@ def main():
                    "shared_experts": cfg.has_shared, "active_expert_slots": active, "token_expert_pairs": pairs,
                    "weights": "FP8 e4m3 + fp32 128x128 block scales, all resident" if fp8 else "bf16, all resident"},
         "roofline": roof, "roofline_gemm2": roof2, "stage_ms": stage_ms,
+        "experts_streamed": n_stream, "experts_tiled": n_tile,
         "layer_weight_gbs": active * (b13 + b2) / (ms_per_step * 1e-3) / 1e9,
     }
     if not args.no_cpu_baseline:

@@ -192,11 +192,16 @@ dwdp_status dwdp_merge_experts(dwdp_ctx* ctx, const dwdp_expert_ptrs* table_host
                                dwdp_expert_ptrs* merged_table_host);
 
 /*
- * Per-stage timing with HIP events on the compute stream.  While enabled, every
- * dwdp_moe_forward records an event before each stage.  dwdp_profile_read synchronises
- * the stream, adds up the elapsed milliseconds per stage over the calls since the last
+ * Per-stage timing with HIP events on the streams the kernels are launched on.  While
+ * enabled, every dwdp_moe_forward records an event before each stage.  dwdp_profile_read
+ * synchronises, adds up the elapsed milliseconds per stage over the calls since the last
  * read into ms_sum[DWDP_N_STAGES] (HOST), stores the number of calls in *n_calls and
  * resets.  At most DWDP_PROFILE_MAX_CALLS calls are kept between reads.
+ * With FP8 weights the grouped GEMMs run as two concurrent chains: GEMM1/GEMM2 are the
+ * weight-streaming kernels on the compute stream (GEMM2 also contains the wait for the
+ * other chain), GEMM1_TILE/GEMM2_TILE the LDS-tiled kernels on an internal stream (on the
+ * compute stream when no expert can be streamed); QUANT includes building the tile list
+ * and any wait for prefetched experts.
  */
 enum {
   DWDP_STAGE_ROUTE = 0,
@@ -205,7 +210,9 @@ enum {
   DWDP_STAGE_GEMM1 = 3,
   DWDP_STAGE_GEMM2 = 4,
   DWDP_STAGE_COMBINE = 5,
-  DWDP_N_STAGES = 6
+  DWDP_STAGE_GEMM1_TILE = 6,
+  DWDP_STAGE_GEMM2_TILE = 7,
+  DWDP_N_STAGES = 8
 };
 enum { DWDP_PROFILE_MAX_CALLS = 512 };
 dwdp_status dwdp_profile_enable(dwdp_ctx* ctx, int32_t on);

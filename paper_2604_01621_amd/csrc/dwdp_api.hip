@@ -18,6 +18,8 @@ struct dwdp_ctx {
   int device = 0;
   hipStream_t compute = nullptr;
   hipStream_t copy = nullptr;
+  hipStream_t aux = nullptr;  // runs the LDS-tiled GEMM chain beside the streaming chain
+  hipEvent_t fork_ev = nullptr, join_ev = nullptr;
   int n_slots = 0;
   size_t rows_max = 0;
   void* ws[DWDP_N_WS] = {};
@@ -36,6 +38,7 @@ struct dwdp_ctx {
   // profiling
   bool prof = false;
   std::vector<hipEvent_t> prof_ev;
+  std::vector<char> prof_has_aux;
   int prof_calls = 0;
   // timeline of prefetch copies and GEMM phases (both streams), relative to tl_base
   struct Span {
@@ -135,6 +138,9 @@ extern "C" dwdp_status dwdp_create(const dwdp_config* cfg, void* compute_stream,
   if (e == hipSuccess) e = hipMalloc((void**)&c->mt_row0, (size_t)c->mt_cap * 4);
   if (e == hipSuccess) e = hipMalloc((void**)&c->n_mtiles, 4);
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->copy, hipStreamNonBlocking);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&c->fork_ev, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&c->join_ev, hipEventDisableTiming);
   c->staged_ev.assign(cfg->n_layers, nullptr);
   for (int l = 0; l < cfg->n_layers && e == hipSuccess; l++)
     e = hipEventCreateWithFlags(&c->staged_ev[l], hipEventDisableTiming);
@@ -170,6 +176,9 @@ extern "C" void dwdp_destroy(dwdp_ctx* c) {
   }
   if (c->tl_base) (void)hipEventDestroy(c->tl_base);
   if (c->copy) (void)hipStreamDestroy(c->copy);
+  if (c->aux) (void)hipStreamDestroy(c->aux);
+  if (c->fork_ev) (void)hipEventDestroy(c->fork_ev);
+  if (c->join_ev) (void)hipEventDestroy(c->join_ev);
   delete c;
 }
 
@@ -228,8 +237,12 @@ extern "C" dwdp_status dwdp_permute(dwdp_ctx* ctx, const int32_t* topk_ids, int3
   return DWDP_OK;
 }
 
-static inline hipEvent_t prof_event(dwdp_ctx* ctx, int stage) {
-  return ctx->prof_ev[(size_t)ctx->prof_calls * (DWDP_N_STAGES + 1) + stage];
+// Profiling events per call: kProfMain+1 on the compute stream (route .. end) and 3 on the aux
+// stream (tile GEMM-1 start, tile GEMM-2 start, end).
+constexpr int kProfMain = 6;
+constexpr int kProfPerCall = kProfMain + 1 + 3;
+static inline hipEvent_t prof_event(dwdp_ctx* ctx, int idx) {
+  return ctx->prof_ev[(size_t)ctx->prof_calls * kProfPerCall + idx];
 }
 
 extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void* x, const float* logits,
@@ -281,24 +294,35 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
   if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM1), s));
   const int span = tl_open(ctx, DWDP_SPAN_GEMM, layer, s);
   if (fp8) {
-    if (use_stream)
+    // Two independent chains: streamed experts on the compute stream, tiled experts on aux.
+    hipStream_t ts_stream = (use_tile && use_stream) ? ctx->aux : s;
+    if (use_tile && use_stream) {
+      HIP_TRY(ctx, hipEventRecord(ctx->fork_ev, s));
+      HIP_TRY(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_ev, 0));
+    }
+    if (use_tile) {
+      if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfMain + 1), ts_stream));
+      launch_gemm1_fp8_tile(ga, ts, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
+                            (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], ts_stream);
+      if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfMain + 2), ts_stream));
+      launch_gemm2_fp8_tile(ga, ts, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
+                            ctx->ws[DWDP_WS_YP], ts_stream);
+      if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfMain + 3), ts_stream));
+      if (use_stream) HIP_TRY(ctx, hipEventRecord(ctx->join_ev, ctx->aux));
+    }
+    if (use_stream) {
       launch_gemm1_fp8(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
                        (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], s);
-    if (use_tile)
-      launch_gemm1_fp8_tile(ga, ts, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
-                            (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], s);
-  } else {
-    launch_gemm1_bf16(ga, x, ctx->ws[DWDP_WS_HQ], s);
-  }
-  if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM2), s));
-  if (fp8) {
-    if (use_stream)
+      if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM2), s));
       launch_gemm2_fp8(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
                        ctx->ws[DWDP_WS_YP], s);
-    if (use_tile)
-      launch_gemm2_fp8_tile(ga, ts, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
-                            ctx->ws[DWDP_WS_YP], s);
+    } else if (prof) {
+      HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM2), s));
+    }
+    if (use_tile && use_stream) HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->join_ev, 0));
   } else {
+    launch_gemm1_bf16(ga, x, ctx->ws[DWDP_WS_HQ], s);
+    if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM2), s));
     launch_gemm2_bf16(ga, ctx->ws[DWDP_WS_HQ], ctx->ws[DWDP_WS_YP], s);
   }
   tl_close(ctx, span, s);
@@ -309,7 +333,8 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
   if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_COMBINE), s));
   launch_combine(ctx->ws[DWDP_WS_YP], !fp8, inv, tw, T, c.H, c.K, c.has_shared, y, s);
   if (prof) {
-    HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_N_STAGES), s));
+    HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfMain), s));
+    ctx->prof_has_aux[ctx->prof_calls] = (fp8 && use_tile) ? 1 : 0;
     ctx->prof_calls++;
   }
   HIP_TRY(ctx, hipGetLastError());
@@ -426,7 +451,8 @@ extern "C" dwdp_status dwdp_pack_fp8_weight(dwdp_ctx* ctx, const void* src, void
 extern "C" dwdp_status dwdp_profile_enable(dwdp_ctx* ctx, int32_t on) {
   if (!ctx) return DWDP_EINVAL;
   if (on && ctx->prof_ev.empty()) {
-    ctx->prof_ev.assign((size_t)DWDP_PROFILE_MAX_CALLS * (DWDP_N_STAGES + 1), nullptr);
+    ctx->prof_ev.assign((size_t)DWDP_PROFILE_MAX_CALLS * kProfPerCall, nullptr);
+    ctx->prof_has_aux.assign(DWDP_PROFILE_MAX_CALLS, 0);
     for (auto& ev : ctx->prof_ev) HIP_TRY(ctx, hipEventCreate(&ev));
   }
   ctx->prof = on != 0;
@@ -438,13 +464,21 @@ extern "C" dwdp_status dwdp_profile_read(dwdp_ctx* ctx, float* ms_sum, int32_t* 
   if (!ctx) return DWDP_EINVAL;
   if (!ms_sum || !n_calls) return fail(ctx, DWDP_EINVAL, "dwdp_profile_read: NULL pointer");
   HIP_TRY(ctx, hipStreamSynchronize(ctx->compute));
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->aux));
   for (int s = 0; s < DWDP_N_STAGES; s++) ms_sum[s] = 0.f;
   for (int i = 0; i < ctx->prof_calls; i++) {
-    for (int s = 0; s < DWDP_N_STAGES; s++) {
+    const hipEvent_t* ev = &ctx->prof_ev[(size_t)i * kProfPerCall];
+    for (int s = 0; s < kProfMain; s++) {
       float ms = 0.f;
-      HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->prof_ev[(size_t)i * (DWDP_N_STAGES + 1) + s],
-                                       ctx->prof_ev[(size_t)i * (DWDP_N_STAGES + 1) + s + 1]));
+      HIP_TRY(ctx, hipEventElapsedTime(&ms, ev[s], ev[s + 1]));
       ms_sum[s] += ms;
+    }
+    if (ctx->prof_has_aux[i]) {
+      float ms = 0.f;
+      HIP_TRY(ctx, hipEventElapsedTime(&ms, ev[kProfMain + 1], ev[kProfMain + 2]));
+      ms_sum[DWDP_STAGE_GEMM1_TILE] += ms;
+      HIP_TRY(ctx, hipEventElapsedTime(&ms, ev[kProfMain + 2], ev[kProfMain + 3]));
+      ms_sum[DWDP_STAGE_GEMM2_TILE] += ms;
     }
   }
   *n_calls = ctx->prof_calls;

@@ -43,28 +43,48 @@ typedef const __attribute__((address_space(4))) float* cf32;
 
 __device__ __forceinline__ v8i cat8(v4i lo, v4i hi) { return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7); }
 
-// One thread lists the M tiles of all experts that have more than stream_max_rows rows.
+// Lists the M tiles (kBM rows each) of all experts that have more than stream_max_rows rows.
+// One block; thread i owns expert slots 2i and 2i+1, an exclusive block scan of the tile
+// counts gives every expert its place in the list.
 __global__ __launch_bounds__(1024) void build_mtile_list_kernel(const int32_t* __restrict__ offsets, int n_slots,
                                                                 int stream_max_rows,
                                                                 int32_t* __restrict__ mt_expert,
                                                                 int32_t* __restrict__ mt_row0,
                                                                 int32_t* __restrict__ n_mtiles, int cap) {
-  __shared__ int32_t off_s[1026];
-  for (int i = threadIdx.x; i <= n_slots; i += blockDim.x) off_s[i] = offsets[i];
+  __shared__ int32_t scan_s[1024];
+  const int tid = threadIdx.x;
+  int cnt[2], r0[2], r1[2];
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+    const int e = 2 * tid + i;
+    cnt[i] = 0;
+    r0[i] = r1[i] = 0;
+    if (e < n_slots) {
+      r0[i] = offsets[e];
+      r1[i] = offsets[e + 1];
+      const int m = r1[i] - r0[i];
+      if (m > stream_max_rows) cnt[i] = (m + kBM - 1) / kBM;
+    }
+  }
+  scan_s[tid] = cnt[0] + cnt[1];
   __syncthreads();
-  if (threadIdx.x == 0) {
-    int n = 0;
-    for (int e = 0; e < n_slots; e++) {
-      const int m = off_s[e + 1] - off_s[e];
-      if (m <= stream_max_rows) continue;
-      for (int r = off_s[e]; r < off_s[e + 1] && n < cap; r += kBM) {
-        mt_expert[n] = e;
-        mt_row0[n] = r;
-        n++;
+  for (int d = 1; d < 1024; d <<= 1) {
+    const int v = (tid >= d) ? scan_s[tid - d] : 0;
+    __syncthreads();
+    scan_s[tid] += v;
+    __syncthreads();
+  }
+  int pos = scan_s[tid] - (cnt[0] + cnt[1]);  // exclusive prefix
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+    for (int k = 0; k < cnt[i]; k++, pos++) {
+      if (pos < cap) {
+        mt_expert[pos] = 2 * tid + i;
+        mt_row0[pos] = r0[i] + k * kBM;
       }
     }
-    *n_mtiles = n;
   }
+  if (tid == 1023) *n_mtiles = min(scan_s[1023], cap);
 }
 
 typedef __attribute__((address_space(1))) const void* gvoid;
