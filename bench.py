@@ -34,7 +34,10 @@ def parse():
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2)
-    ap.add_argument("--slice-mib", type=int, default=64, help="pipeline workload: prefetch slice size in MiB")
+    ap.add_argument("--slice-mib", type=int, default=1, help="pipeline workload: prefetch slice size in MiB")
+    ap.add_argument("--copy-engine", type=int, default=1, help="pipeline workload: 0 hipMemcpyAsync per slice, "
+                                                               "1 copy-plan kernel")
+    ap.add_argument("--copy-wgs", type=int, default=512, help="pipeline workload: workgroups of the copy-plan kernel")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="after the timed region run one plain device copy of this many MiB (a known-size "
                          "reference dispatch for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")

@@ -171,6 +171,21 @@ dwdp_status dwdp_set_stream_max_rows(dwdp_ctx* ctx, int32_t max_rows);
 dwdp_status dwdp_pack_fp8_weight(dwdp_ctx* ctx, const void* src, void* dst, int64_t rows, int64_t cols);
 
 /*
+ * How dwdp_prefetch_layer moves the bytes of its copy plan.
+ *   DWDP_COPY_MEMCPY (default): one hipMemcpyAsync (device to device) per plan entry, the
+ *     counterpart of the copy-engine cudaMemcpyAsync pulls of paper Section 2.  Each entry
+ *     costs a runtime call, so small slices are launch-bound.
+ *   DWDP_COPY_KERNEL: the whole plan is executed by one kernel launch of at most
+ *     n_workgroups workgroups that walk the plan in order (entries cut into pieces of at
+ *     most 256 KiB).  The slice order of the plan is kept, the slice size costs nothing,
+ *     and n_workgroups bounds how many compute units the copy takes from the GEMMs.
+ *     The device copy of a layer's plan is built on the first call with given arguments
+ *     (a synchronous upload) and reused while the arguments stay the same.
+ */
+enum { DWDP_COPY_MEMCPY = 0, DWDP_COPY_KERNEL = 1 };
+dwdp_status dwdp_set_copy_engine(dwdp_ctx* ctx, int32_t mode, int32_t n_workgroups);
+
+/*
  * Host-only: the copy plan dwdp_prefetch_layer would issue, written to HOST arrays of
  * capacity `cap` entries (may be NULL with cap = 0 to query the length).  *n_out receives
  * the plan length.  Same argument meaning as dwdp_prefetch_layer.  Touches no GPU.

@@ -60,6 +60,7 @@ def _load() -> C.CDLL:
     lib.dwdp_merge_experts.argtypes = [vp, C.POINTER(dwdp_expert_ptrs), i32, vp, vp, vp, vp,
                                        C.POINTER(dwdp_expert_ptrs)]
     lib.dwdp_set_stream_max_rows.argtypes = [vp, i32]
+    lib.dwdp_set_copy_engine.argtypes = [vp, i32, i32]
     lib.dwdp_pack_fp8_weight.argtypes = [vp, vp, vp, C.c_int64, C.c_int64]
     lib.dwdp_profile_enable.argtypes = [vp, i32]
     lib.dwdp_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32)]
@@ -169,6 +170,10 @@ class Context:
         self._check(lib.dwdp_merge_experts(self.h, src, n, _ptr(w13_out), _ptr(s13_out), _ptr(w2_out), _ptr(s2_out),
                                            dst))
         return merged
+
+    def dwdp_set_copy_engine(self, mode: int, n_workgroups: int = 256):
+        """mode 0: hipMemcpyAsync per plan entry; mode 1: one copy-plan kernel of n_workgroups."""
+        self._check(lib.dwdp_set_copy_engine(self.h, mode, n_workgroups))
 
     def dwdp_set_stream_max_rows(self, max_rows: int):
         self._check(lib.dwdp_set_stream_max_rows(self.h, max_rows))

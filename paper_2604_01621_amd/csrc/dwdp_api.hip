@@ -30,6 +30,15 @@ struct dwdp_ctx {
   int32_t* mt_row0 = nullptr;
   int32_t* n_mtiles = nullptr;
   int mt_cap = 0;
+  // prefetch engine: 0 = one hipMemcpyAsync per plan entry, 1 = one copy-plan kernel launch
+  int copy_mode = 0;
+  int copy_wgs = 256;
+  struct PlanCache {
+    std::vector<uintptr_t> key;  // the arguments the cached plan was built from
+    CopyUnit* units = nullptr;   // device
+    int n_units = 0;
+  };
+  std::vector<PlanCache> plan_cache;  // per layer
   // double-buffer protocol
   std::vector<hipEvent_t> staged_ev;  // per layer: its prefetch copies are complete
   hipEvent_t done_ev[2] = {nullptr, nullptr};  // per staging buffer: its last reader finished
@@ -141,6 +150,7 @@ extern "C" dwdp_status dwdp_create(const dwdp_config* cfg, void* compute_stream,
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&c->fork_ev, hipEventDisableTiming);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&c->join_ev, hipEventDisableTiming);
+  c->plan_cache.resize(cfg->n_layers);
   c->staged_ev.assign(cfg->n_layers, nullptr);
   for (int l = 0; l < cfg->n_layers && e == hipSuccess; l++)
     e = hipEventCreateWithFlags(&c->staged_ev[l], hipEventDisableTiming);
@@ -164,6 +174,8 @@ extern "C" void dwdp_destroy(dwdp_ctx* c) {
   if (c->mt_expert) (void)hipFree(c->mt_expert);
   if (c->mt_row0) (void)hipFree(c->mt_row0);
   if (c->n_mtiles) (void)hipFree(c->n_mtiles);
+  for (auto& pc : c->plan_cache)
+    if (pc.units) (void)hipFree(pc.units);
   for (hipEvent_t ev : c->staged_ev)
     if (ev) (void)hipEventDestroy(ev);
   for (hipEvent_t ev : c->done_ev)
@@ -391,9 +403,47 @@ extern "C" dwdp_status dwdp_prefetch_layer(dwdp_ctx* ctx, int32_t layer, const v
   dwdp_build_copy_plan(src, dst, bytes, n_peers, n_params, slice_bytes, pd.data(), ps.data(), pb.data(), n, &n);
   // double buffering: the buffer is free once its previous reader has finished
   if (ctx->done_valid[b]) HIP_TRY(ctx, hipStreamWaitEvent(ctx->copy, ctx->done_ev[b], 0));
+  if (ctx->copy_mode == 1) {
+    // The plan of a layer is static (same regions every iteration): build its device copy once.
+    std::vector<uintptr_t> key;
+    key.push_back((uintptr_t)n_peers);
+    key.push_back((uintptr_t)n_params);
+    key.push_back((uintptr_t)slice_bytes);
+    for (int i = 0; i < n_peers * n_params; i++) {
+      key.push_back((uintptr_t)src[i]);
+      key.push_back((uintptr_t)dst[i]);
+    }
+    for (int p = 0; p < n_params; p++) key.push_back((uintptr_t)bytes[p]);
+    dwdp_ctx::PlanCache& pc = ctx->plan_cache[layer];
+    if (pc.key != key) {
+      // plan entries are cut into units of at most 256 KiB so that the workgroups share evenly
+      const size_t unit = 256 << 10;
+      std::vector<CopyUnit> units;
+      for (size_t i = 0; i < n; i++)
+        for (size_t o = 0; o < pb[i]; o += unit)
+          units.push_back(CopyUnit{(char*)pd[i] + o, (const char*)ps[i] + o, pb[i] - o < unit ? pb[i] - o : unit});
+      if (pc.units) {
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->copy));  // an earlier launch may still read the old plan
+        HIP_TRY(ctx, hipFree(pc.units));
+        pc.units = nullptr;
+      }
+      pc.key.clear();
+      if (!units.empty()) {
+        HIP_TRY(ctx, hipMalloc((void**)&pc.units, units.size() * sizeof(CopyUnit)));
+        HIP_TRY(ctx, hipMemcpy(pc.units, units.data(), units.size() * sizeof(CopyUnit), hipMemcpyHostToDevice));
+      }
+      pc.n_units = (int)units.size();
+      pc.key = key;
+    }
+  }
   const int span = tl_open(ctx, DWDP_SPAN_COPY, layer, ctx->copy);
-  for (size_t i = 0; i < n; i++)
-    HIP_TRY(ctx, hipMemcpyAsync(pd[i], ps[i], pb[i], hipMemcpyDeviceToDevice, ctx->copy));
+  if (ctx->copy_mode == 1) {
+    launch_copy_plan(ctx->plan_cache[layer].units, ctx->plan_cache[layer].n_units, ctx->copy_wgs, ctx->copy);
+    HIP_TRY(ctx, hipGetLastError());
+  } else {
+    for (size_t i = 0; i < n; i++)
+      HIP_TRY(ctx, hipMemcpyAsync(pd[i], ps[i], pb[i], hipMemcpyDeviceToDevice, ctx->copy));
+  }
   tl_close(ctx, span, ctx->copy);
   HIP_TRY(ctx, hipEventRecord(ctx->staged_ev[layer], ctx->copy));
   ctx->pending_layer[b] = layer;
@@ -426,6 +476,17 @@ extern "C" dwdp_status dwdp_merge_experts(dwdp_ctx* ctx, const dwdp_expert_ptrs*
     }
     merged_table_host[e] = m;
   }
+  return DWDP_OK;
+}
+
+extern "C" dwdp_status dwdp_set_copy_engine(dwdp_ctx* ctx, int32_t mode, int32_t n_workgroups) {
+  if (!ctx) return DWDP_EINVAL;
+  if (mode != DWDP_COPY_MEMCPY && mode != DWDP_COPY_KERNEL)
+    return fail(ctx, DWDP_EINVAL, "dwdp_set_copy_engine: unknown mode %d", mode);
+  if (mode == DWDP_COPY_KERNEL && (n_workgroups < 1 || n_workgroups > 65535))
+    return fail(ctx, DWDP_EINVAL, "dwdp_set_copy_engine: n_workgroups must be in [1,65535]");
+  ctx->copy_mode = mode;
+  if (mode == DWDP_COPY_KERNEL) ctx->copy_wgs = n_workgroups;
   return DWDP_OK;
 }
 

@@ -35,6 +35,15 @@ void launch_permute(const int32_t* ids, int T, int E, int K, int has_shared, int
 // x bf16 [T,H] -> xq fp8 [T,H], xs fp32 [T,H/128]
 void launch_quant_act(const void* x, int T, int H, uint8_t* xq, float* xs, hipStream_t stream);
 
+// One piece of a copy plan (device pointers).
+struct CopyUnit {
+  void* dst;
+  const void* src;
+  size_t bytes;
+};
+// units: device array, plan order; at most n_workgroups workgroups are launched.
+void launch_copy_plan(const CopyUnit* units, int n_units, int n_workgroups, hipStream_t stream);
+
 // y[t] = sum_k w[t,k] * yp[inv_perm[t*K+k]] (+ yp[T*K+t]); yp bf16 or fp32 [rows,H]; y bf16 [T,H]
 void launch_combine(const void* yp, bool yp_fp32, const int32_t* inv_perm, const float* topk_w, int T, int H, int K,
                     int has_shared, void* y, hipStream_t stream);

@@ -1,13 +1,13 @@
 // LDS-tiled FP8 grouped GEMM for gfx950: the large-M (prefill-shaped) path.
 //
-// A workgroup of 8 waves computes a 256 (weight rows) x 288 (tokens) output tile of one
+// A workgroup of 12 waves computes a 256 (weight rows) x 288 (tokens) output tile of one
 // expert.  288 tokens cover almost every expert of the prefill workload (256 +- 16 rows), so
 // each weight panel is read from HBM once; with 128-token tiles the panels were re-read by
 // every M tile and the kernel ran at HBM speed.  Per 128-wide K block -- exactly one
 // weight-scale block and one activation-scale group -- the workgroup stages 16 packed
 // weight tiles (32 KiB, contiguous 2 KiB pieces located through the expert-pointer table)
 // and up to 18 packed token tiles (36 KiB, rows gathered through the permutation) in LDS;
-// wave (wn, wm) multiplies weight tiles 4*wn..4*wn+3 with token tiles wm, wm+2, ... on
+// wave (wn, wm) multiplies weight tiles 4*wn..4*wn+3 with token tiles wm, wm+3, ... on
 // v_mfma_f32_16x16x128_f8f6f4 and folds every fp32 partial product into its accumulator
 // with s_act[token,kb] * s_w[nblock,kb] on the VALU.  The LDS image of K block kb+1 is
 // filled by asynchronous global->LDS copies (global_load_lds_dwordx4, no staging registers,
@@ -24,16 +24,25 @@
 // epilogue bf16 store.  Experts with few rows are left to the streaming kernels (they are not listed).
 #include "dwdp_kernels.h"
 
+// Timing experiments only (results are wrong when set): 1 = skip the MFMA/VALU work,
+// 2 = skip the global->LDS copies after the first K block, 4 = skip the weight copies,
+// 8 = skip the token copies.  Never set in a product build.
+#ifndef DWDP_TILE_DBG
+#define DWDP_TILE_DBG 0
+#endif
+
 namespace dwdp {
 
 constexpr int kBM = 288;          // tokens per workgroup tile
 constexpr int kTT = kBM / 16;     // token tiles per workgroup (18)
-constexpr int kTW = kTT / 2;      // token tiles per wave (9)
-constexpr int kTileThreads = 512;
+constexpr int kWM = 3;            // waves along the token dimension (x 4 along the weight rows)
+constexpr int kTW = (kTT + kWM - 1) / kWM;  // token tiles per wave
+constexpr int kTileWaves = 4 * kWM;
+constexpr int kTileThreads = 64 * kTileWaves;
 constexpr int kLdsA = 16 * kTileBytes;
 constexpr int kLdsB = kTT * kTileBytes;
 constexpr int kSaLen = 320;
-static_assert(kBM <= kSaLen && kTT <= 20 && kTT % 2 == 0, "copy loops cover 40 token half-tiles and 320 scales");
+static_assert(kBM <= kSaLen && kTT <= 20, "copy loops cover 40 token half-tiles and 320 scales");
 
 typedef const __attribute__((address_space(1))) v4i* gv4i;
 typedef const __attribute__((address_space(1))) float* gf32;
@@ -113,6 +122,7 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   __shared__ __attribute__((aligned(16))) float lds_sa0[kSaLen];  // 5 waves x 64 activation scales
   __shared__ __attribute__((aligned(16))) float lds_sa1[kSaLen];
   __shared__ float lds_amax[4 * kBM];
+  __shared__ int32_t lds_row[kSaLen];
 
   const int xcd = blockIdx.x & 7;
   const int s = blockIdx.x >> 3;
@@ -130,7 +140,7 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63, lr = lane & 15, lq = lane >> 4;
-  const int wn = wave & 3, wm = wave >> 2;
+  const int wn = wave & 3, wm = wave >> 2;  // wm < kWM
   const int Kdim = G1 ? H : I;  // reduction length
   const int nkb = Kdim / 128;
   const int n_tile_rows = (G1 ? 2 * I : H) / 16;
@@ -138,34 +148,30 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   const float* sbase = G1 ? table[e].s13 : table[e].s2;
 
   // ---- copy sources (fixed over the K loop) ----
-  // weights: wave w copies LDS tiles 2w and 2w+1 (4 pieces of 1 KiB); LDS tile a = wn*4 + j
-  const uint8_t* a_src[2];
+  // weights: 32 pieces of 1 KiB (16 LDS tiles x 2 halves), kAP per wave; LDS tile a = wn*4 + j
+  constexpr int kAP = (32 + kTileWaves - 1) / kTileWaves;
+  const uint8_t* a_src[kAP];
 #pragma unroll
-  for (int i = 0; i < 2; i++) {
-    const int a = wave * 2 + i;
+  for (int i = 0; i < kAP; i++) {
+    const int c = min(wave + kTileWaves * i, 31);  // piece: tile c/2, half c&1
+    const int a = c >> 1;
     const int w = a >> 2, j = a & 3;
     int tr;
     if (G1)
       tr = (j < 2 ? 0 : I / 16) + panel * 8 + 2 * w + (j & 1);
     else
       tr = min(panel * 16 + a, n_tile_rows - 1);
-    a_src[i] = wbase + (size_t)tr * nkb * kTileBytes + lane * 16;
+    a_src[i] = wbase + (size_t)tr * nkb * kTileBytes + (c & 1) * (kTileBytes / 2);  // wave-uniform
   }
-  // tokens: wave w copies 1 KiB pieces c = w, w+8, ... (piece c = token tile c/2, half c&1)
-  uint32_t b_src[5];
-#pragma unroll
-  for (int i = 0; i < 5; i++) {
-    const int c = wave + 8 * i;
-    const int row = min(r0 + (c >> 1) * 16 + lr, r_end - 1);
-    const int src_row = G1 ? ((e < E) ? perm[row] / K : row - T * K) : row;
-    b_src[i] = (uint32_t)src_row * Kdim + lq * 32 + (c & 1) * 16;
+  // tokens: wave w copies 1 KiB pieces c = w, w+kTileWaves, ... (piece c = token tile c/2, half c&1)
+  // The source row of every token of the tile is kept in LDS (not in registers) and looked
+  // up again by each copy: lds_row[i] = row of act / act_s that token i reads.
+  constexpr int kBP = (2 * kTT + kTileWaves - 1) / kTileWaves;
+  for (int i = tid; i < kSaLen; i += kTileThreads) {
+    const int row = min(r0 + i, r_end - 1);
+    lds_row[i] = G1 ? ((e < E) ? perm[row] / K : row - T * K) : row;
   }
-  const float* sa_src;
-  {
-    const int row = min(r0 + min(wave, 4) * 64 + lane, r_end - 1);
-    const int src_row = G1 ? ((e < E) ? perm[row] / K : row - T * K) : row;
-    sa_src = act_s + (size_t)src_row * nkb;
-  }
+  __syncthreads();
   // scale rows of this wave's tiles: G1 gate block / up block; GEMM-2 one block per wave pair
   const float* sw0;
   const float* sw1;
@@ -185,35 +191,40 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
 
   auto issue = [&](uint8_t* la, uint8_t* lb, float* lsa, int kb) {
 #pragma unroll
-    for (int i = 0; i < 2; i++) {
-      const uint8_t* p = a_src[i] + (size_t)kb * kTileBytes;
-      dma16(p, la + (wave * 2 + i) * kTileBytes);
-      dma16(p + kTileBytes / 2, la + (wave * 2 + i) * kTileBytes + kTileBytes / 2);
+    for (int i = 0; i < kAP; i++) {
+      const int c = wave + kTileWaves * i;
+      if (c < 32 && !(DWDP_TILE_DBG & 4))
+        dma16(a_src[i] + (size_t)kb * kTileBytes + lane * 16, la + c * (kTileBytes / 2));
     }
 #pragma unroll
-    for (int i = 0; i < 5; i++) {
-      const int c = wave + 8 * i;
-      if (c < 2 * ntt) dma16(act + (b_src[i] + (uint32_t)kb * 128), lb + c * (kTileBytes / 2));
+    for (int i = 0; i < kBP; i++) {
+      const int c = wave + kTileWaves * i;
+      if (c < 2 * ntt && !(DWDP_TILE_DBG & 8)) {
+        const uint32_t off = (uint32_t)lds_row[(c >> 1) * 16 + lr] * Kdim + lq * 32 + (c & 1) * 16 + kb * 128;
+        dma16(act + off, lb + c * (kTileBytes / 2));
+      }
     }
-    if (wave < 5) dma4(sa_src + kb, lsa + wave * 64);
+    if (wave < 5) dma4(act_s + (size_t)lds_row[wave * 64 + lane] * nkb + kb, lsa + wave * 64);
   };
 
   auto compute = [&](const uint8_t* la, const uint8_t* lb, const float* lsa, int kb) {
     const float w0 = *(cf32)(sw0 + kb);
     const float w1 = *(cf32)(sw1 + kb);
+    // one per-lane base per LDS array; every tile is a compile-time offset from it
+    const uint8_t* pa = la + wn * 4 * kTileBytes + lane * 16;
+    const uint8_t* pb = lb + wm * kTileBytes + lane * 16;
+    const float* ps = lsa + wm * 16 + lr;
     v8i af[4];
 #pragma unroll
-    for (int j = 0; j < 4; j++) {
-      const uint8_t* p = la + (wn * 4 + j) * kTileBytes + lane * 16;
-      af[j] = cat8(*(const v4i*)p, *(const v4i*)(p + kTileBytes / 2));
-    }
+    for (int j = 0; j < 4; j++)
+      af[j] = cat8(*(const v4i*)(pa + j * kTileBytes), *(const v4i*)(pa + j * kTileBytes + kTileBytes / 2));
 #pragma unroll
     for (int ti = 0; ti < kTW; ti++) {
-      const int t = wm + 2 * ti;
+      const int t = wm + kWM * ti;
       if (t < ntt) {
-        const uint8_t* p = lb + t * kTileBytes + lane * 16;
+        const uint8_t* p = pb + ti * (kWM * kTileBytes);
         const v8i bf = cat8(*(const v4i*)p, *(const v4i*)(p + kTileBytes / 2));
-        const float sa = lsa[t * 16 + lr];
+        const float sa = ps[ti * (kWM * 16)];
         const float s0 = sa * w0, s1 = sa * w1;
 #pragma unroll
         for (int j = 0; j < 4; j++) {
@@ -232,12 +243,12 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   issue(lds_a0, lds_b0, lds_sa0, 0);
   for (int kb = 0; kb < nkb; kb += 2) {
     __syncthreads();
-    if (kb + 1 < nkb) issue(lds_a1, lds_b1, lds_sa1, kb + 1);
-    compute(lds_a0, lds_b0, lds_sa0, kb);
+    if (kb + 1 < nkb && !(DWDP_TILE_DBG & 2)) issue(lds_a1, lds_b1, lds_sa1, kb + 1);
+    if (!(DWDP_TILE_DBG & 1)) compute(lds_a0, lds_b0, lds_sa0, kb);
     if (kb + 1 < nkb) {
       __syncthreads();
-      if (kb + 2 < nkb) issue(lds_a0, lds_b0, lds_sa0, kb + 2);
-      compute(lds_a1, lds_b1, lds_sa1, kb + 1);
+      if (kb + 2 < nkb && !(DWDP_TILE_DBG & 2)) issue(lds_a0, lds_b0, lds_sa0, kb + 2);
+      if (!(DWDP_TILE_DBG & 1)) compute(lds_a1, lds_b1, lds_sa1, kb + 1);
     }
   }
 
@@ -246,7 +257,7 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
     // h = silu(gate) * up, kept in acc[0..1]
 #pragma unroll
     for (int ti = 0; ti < kTW; ti++) {
-      const int t = wm + 2 * ti;
+      const int t = wm + kWM * ti;
       float amax = 0.f;
       if (t < ntt) {
 #pragma unroll
@@ -261,12 +272,12 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
       }
       amax = fmaxf(amax, __shfl_xor(amax, 16));
       amax = fmaxf(amax, __shfl_xor(amax, 32));
-      if (lq == 0) lds_amax[wn * kBM + t * 16 + lr] = amax;
+      if (lq == 0 && t < kTT) lds_amax[wn * kBM + t * 16 + lr] = amax;
     }
     __syncthreads();
 #pragma unroll
     for (int ti = 0; ti < kTW; ti++) {
-      const int t = wm + 2 * ti;
+      const int t = wm + kWM * ti;
       if (t < ntt) {
         const int tok = t * 16 + lr;
         const float amax = fmaxf(fmaxf(lds_amax[tok], lds_amax[kBM + tok]),
@@ -291,7 +302,7 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
       if (n0 < H) {
 #pragma unroll
         for (int ti = 0; ti < kTW; ti++) {
-          const int t = wm + 2 * ti;
+          const int t = wm + kWM * ti;
           const int r = r0 + t * 16 + lr;
           if (t < ntt && r < r_end) {
             uint2 o;

@@ -97,6 +97,43 @@ __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ y
   }
 }
 
+// Executes a copy plan in one launch: unit u (dst, src, bytes) is copied by workgroup
+// u % gridDim.x, units in plan order, so the slice interleaving of the plan is kept while the
+// number of workgroups bounds how much of the chip the copy occupies.
+__global__ __launch_bounds__(256) void copy_plan_kernel(const CopyUnit* __restrict__ units, int n_units) {
+  for (int u = blockIdx.x; u < n_units; u += gridDim.x) {
+    const CopyUnit cu = units[u];
+    const uint8_t* src = (const uint8_t*)cu.src;
+    uint8_t* dst = (uint8_t*)cu.dst;
+    size_t done = 0;
+    if ((((uintptr_t)src | (uintptr_t)dst) & 15) == 0) {
+      const size_t n16 = cu.bytes >> 4;
+      const v4i* s16 = (const v4i*)src;
+      v4i* d16 = (v4i*)dst;
+      size_t i = threadIdx.x;
+      for (; i + 3 * 256 < n16; i += 4 * 256) {  // four 16-byte loads in flight per lane
+        const v4i a = __builtin_nontemporal_load(s16 + i);
+        const v4i b = __builtin_nontemporal_load(s16 + i + 256);
+        const v4i c = __builtin_nontemporal_load(s16 + i + 512);
+        const v4i d = __builtin_nontemporal_load(s16 + i + 768);
+        __builtin_nontemporal_store(a, d16 + i);
+        __builtin_nontemporal_store(b, d16 + i + 256);
+        __builtin_nontemporal_store(c, d16 + i + 512);
+        __builtin_nontemporal_store(d, d16 + i + 768);
+      }
+      for (; i < n16; i += 256) d16[i] = s16[i];
+      done = n16 << 4;
+    }
+    for (size_t i = done + threadIdx.x; i < cu.bytes; i += 256) dst[i] = src[i];
+  }
+}
+
+void launch_copy_plan(const CopyUnit* units, int n_units, int n_workgroups, hipStream_t stream) {
+  if (n_units <= 0) return;
+  const int g = n_units < n_workgroups ? n_units : n_workgroups;
+  hipLaunchKernelGGL(copy_plan_kernel, dim3(g), dim3(256), 0, stream, units, n_units);
+}
+
 void launch_combine(const void* yp, bool yp_fp32, const int32_t* inv_perm, const float* topk_w, int T, int H, int K,
                     int has_shared, void* y, hipStream_t stream) {
   if (T <= 0) return;

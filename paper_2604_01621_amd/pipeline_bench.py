@@ -36,9 +36,12 @@ def run(args):
     dev = torch.device("cuda:0")
     cfg = inputs.WORKLOADS["pipeline"] if args.T is None else inputs.WORKLOADS["pipeline"].with_T(args.T)
     n_layers, n_res, n_peers = 4, 64, 3
-    slice_bytes = getattr(args, "slice_mib", 64) << 20
+    slice_bytes = getattr(args, "slice_mib", 1) << 20
     stream = torch.cuda.Stream()
     ctx = binding.Context(cfg, n_layers=n_layers, stream=stream)
+    engine = getattr(args, "copy_engine", 1)
+    copy_wgs = getattr(args, "copy_wgs", 512)
+    ctx.dwdp_set_copy_engine(engine, copy_wgs)
     layers = pipeline.SplitWeightLayers(ctx, cfg, n_layers, n_res, n_peers, seed=args.seed, device=dev)
     layers.drop_logical()
     torch.cuda.empty_cache()
@@ -109,6 +112,7 @@ def run(args):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8_e4m3", "data": "synthetic",
         "config": {"workload": "pipeline: 4 DeepSeek-R1-shaped MoE layers, 64 resident + 192 staged experts each",
                    "T": cfg.T, "layers": n_layers, "slice_bytes": slice_bytes, "active_expert_slots": active,
+                   "copy_engine": "copy-plan kernel, %d workgroups" % copy_wgs if engine == 1 else "hipMemcpyAsync per slice",
                    "prefetch_bytes_per_layer": pf_bytes},
         "ms_per_layer": ms_per_layer, "compute_alone_ms_per_layer": compute_alone_ms,
         "copy_alone_ms_per_layer": copy_alone_ms, "copy_alone_gbs": pf_bytes / (copy_alone_ms * 1e-3) / 1e9,

@@ -43,10 +43,12 @@ def _reference_outputs(ctx, cfg, layers, xs, lgs, bs):
     return out
 
 
-@pytest.mark.parametrize("slice_bytes", [0, 4096, 100000])
-def test_pipeline_poisoned_and_delayed(env, slice_bytes):
+@pytest.mark.parametrize("engine", [0, 1])
+@pytest.mark.parametrize("slice_bytes", [0, 4096, 100000, 1000])
+def test_pipeline_poisoned_and_delayed(env, slice_bytes, engine):
     binding, pipeline, cfg, ctx, layers, xs, lgs, bs = env
-    print("pipeline slice", slice_bytes, flush=True)
+    print("pipeline slice", slice_bytes, "engine", engine, flush=True)
+    ctx.dwdp_set_copy_engine(engine, 24)
     ref = _reference_outputs(ctx, cfg, layers, xs, lgs, bs)
     copy_stream = torch.cuda.ExternalStream(ctx.copy_stream_handle())
     ys = [[torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device="cuda") for _ in range(N_LAYERS)] for _ in range(2)]
@@ -77,6 +79,7 @@ def test_pipeline_poisoned_and_delayed(env, slice_bytes):
                 ev.record(torch.cuda.current_stream())
                 done[b] = ev
     torch.cuda.synchronize()
+    ctx.dwdp_set_copy_engine(0)
     for it in range(2):
         for l in range(N_LAYERS):
             got = ys[it][l].float().cpu().numpy()
