@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2)
     ap.add_argument("--slice-mib", type=int, default=1, help="pipeline workload: prefetch slice size in MiB")
+    ap.add_argument("--stream-max-rows", type=int, default=None,
+                    help="override the library's kernel-selection threshold (dwdp_set_stream_max_rows)")
     ap.add_argument("--copy-engine", type=int, default=1, help="pipeline workload: 0 hipMemcpyAsync per slice, "
                                                                "1 copy-plan kernel")
     ap.add_argument("--copy-wgs", type=int, default=512, help="pipeline workload: workgroups of the copy-plan kernel")
@@ -95,6 +97,8 @@ def main():
     w = inputs.make_expert_weights(cfg, args.seed, device=dev)
     stream = torch.cuda.Stream()
     ctx = binding.Context(cfg, stream=stream)
+    if args.stream_max_rows is not None:
+        ctx.dwdp_set_stream_max_rows(args.stream_max_rows)
     wp = ctx.pack_experts(w)          # one-off weight preparation, outside the timed region
     table = binding.expert_table(wp)
     y = torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device=dev)
@@ -134,7 +138,9 @@ def main():
     b13 = 2 * cfg.I * cfg.H * el + (4 * (2 * cfg.I // 128) * (cfg.H // 128) if fp8 else 0)
     b2 = cfg.H * cfg.I * el + (4 * (cfg.H // 128) * (cfg.I // 128) if fp8 else 0)
     # which kernel family serves which expert (the library's default threshold: 16 rows)
-    smr = 16 if (fp8 and cfg.T > 16) else (1 << 30)
+    smr = args.stream_max_rows if args.stream_max_rows is not None else 16
+    if not fp8 or cfg.T <= smr:
+        smr = 1 << 30
     n_stream = int(((counts > 0) & (counts <= smr)).sum())
     n_tile = int((counts > smr).sum())
     rows_tile = int(counts[counts > smr].sum())

@@ -172,11 +172,14 @@ __global__ __launch_bounds__(kStreamThreads, 2) void gemm1_fp8_stream_kernel(
   }
 }
 
-// Task = (expert slot e, block nb of 128 output rows).  Wave w owns rows nb*128 + w*32 + {0..31}.
+// Task = (expert slot e, block nb of kG2Rows output rows).  Wave w owns kG2Tiles consecutive
+// 16-row tiles, all inside one 128-row scale block.
+constexpr int kG2Tiles = 2;
+constexpr int kG2Rows = 4 * kG2Tiles * 16;  // rows per workgroup (128)
 __global__ __launch_bounds__(kStreamThreads, 2) void gemm2_fp8_stream_kernel(
     const dwdp_expert_ptrs* __restrict__ table, const int32_t* __restrict__ offsets, const uint8_t* __restrict__ hq,
     const float* __restrict__ hs, uint16_t* __restrict__ yp, int H, int I, int max_rows) {
-  const int nnb = H / 128;
+  const int nnb = (H + kG2Rows - 1) / kG2Rows;
   const int e = blockIdx.x / nnb;
   const int nb = blockIdx.x - e * nnb;
   const int r0 = offsets[e];
@@ -184,30 +187,31 @@ __global__ __launch_bounds__(kStreamThreads, 2) void gemm2_fp8_stream_kernel(
   if (r1 <= r0 || r1 - r0 > max_rows) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 15, lq = lane >> 4;
   const int nkb = I / 128;
+  const int row0 = nb * kG2Rows + wave * (kG2Tiles * 16);  // first output row of this wave
+  if (row0 >= H) return;                                   // H is a multiple of 128, not of 256
   const uint8_t* w2 = (const uint8_t*)table[e].w2;
   const float* s2 = table[e].s2;
-  const uint8_t* wt[2];
+  const uint8_t* wt[kG2Tiles];
 #pragma unroll
-  for (int j = 0; j < 2; j++)
-    wt[j] = w2 + (size_t)(nb * 8 + wave * 2 + j) * nkb * kTileBytes + lane * 16;
-  const float* swp[1] = {s2 + (size_t)nb * nkb};
+  for (int j = 0; j < kG2Tiles; j++) wt[j] = w2 + (size_t)(row0 / 16 + j) * nkb * kTileBytes + lane * 16;
+  const float* swp[1] = {s2 + (size_t)(row0 / 128) * nkb};
 
   for (int rt = r0; rt < r1; rt += 16) {
     const int r = rt + lr;
     const int rc = min(r, r1 - 1);
     const uint8_t* xrow = hq + (size_t)rc * I + lq * 32;
     const float* xsrow = hs + (size_t)rc * nkb;
-    v4f acc[2];
-    acc[0] = (v4f){0.f, 0.f, 0.f, 0.f};
-    acc[1] = (v4f){0.f, 0.f, 0.f, 0.f};
-    stream_mainloop<2, 1>(wt, swp, xrow, xsrow, nkb, acc);
+    v4f acc[kG2Tiles];
+#pragma unroll
+    for (int j = 0; j < kG2Tiles; j++) acc[j] = (v4f){0.f, 0.f, 0.f, 0.f};
+    stream_mainloop<kG2Tiles, 1>(wt, swp, xrow, xsrow, nkb, acc);
     if (r < r1) {
 #pragma unroll
-      for (int j = 0; j < 2; j++) {
+      for (int j = 0; j < kG2Tiles; j++) {
         uint2 o;
         o.x = (uint32_t)f32_to_bf16(acc[j][0]) | ((uint32_t)f32_to_bf16(acc[j][1]) << 16);
         o.y = (uint32_t)f32_to_bf16(acc[j][2]) | ((uint32_t)f32_to_bf16(acc[j][3]) << 16);
-        *(uint2*)(yp + (size_t)r * H + nb * 128 + wave * 32 + j * 16 + lq * 4) = o;
+        *(uint2*)(yp + (size_t)r * H + row0 + j * 16 + lq * 4) = o;
       }
     }
   }
@@ -224,7 +228,7 @@ void launch_gemm1_fp8(const GemmArgs& a, int max_rows, const uint8_t* xq, const 
 void launch_gemm2_fp8(const GemmArgs& a, int max_rows, const uint8_t* hq, const float* hs, void* yp,
                       hipStream_t stream) {
   if (a.T <= 0) return;
-  dim3 grid(a.n_slots * (a.H / 128));
+  dim3 grid(a.n_slots * ((a.H + kG2Rows - 1) / kG2Rows));
   hipLaunchKernelGGL(gemm2_fp8_stream_kernel, grid, dim3(kStreamThreads), 0, stream, a.table, a.offsets, hq, hs,
                      (uint16_t*)yp, a.H, a.I, max_rows);
 }
