@@ -1,53 +1,76 @@
 // LDS-tiled FP8 grouped GEMM for gfx950: the large-M (prefill-shaped) path.
 //
-// A workgroup of 12 waves computes a 256 (weight rows) x 288 (tokens) output tile of one
-// expert.  288 tokens cover almost every expert of the prefill workload (256 +- 16 rows), so
-// each weight panel is read from HBM once; with 128-token tiles the panels were re-read by
-// every M tile and the kernel ran at HBM speed.  Per 128-wide K block -- exactly one
-// weight-scale block and one activation-scale group -- the workgroup stages 16 packed
-// weight tiles (32 KiB, contiguous 2 KiB pieces located through the expert-pointer table)
-// and up to 18 packed token tiles (36 KiB, rows gathered through the permutation) in LDS;
-// wave (wn, wm) multiplies weight tiles 4*wn..4*wn+3 with token tiles wm, wm+3, ... on
-// v_mfma_f32_16x16x128_f8f6f4 and folds every fp32 partial product into its accumulator
-// with s_act[token,kb] * s_w[nblock,kb] on the VALU.  The LDS image of K block kb+1 is
-// filled by asynchronous global->LDS copies (global_load_lds_dwordx4, no staging registers,
-// no ds_write) while block kb is multiplied; two images of 68 KiB alternate, one barrier
-// per K block.
+// A workgroup of 8 waves computes a 256 (weight rows) x 288 (tokens) output tile of one
+// expert; 288 tokens cover almost every expert of the prefill workload (256 +- 16 rows),
+// so each weight panel is read from HBM once.  Per 128-wide K block -- exactly one
+// weight-scale block and one activation-scale group:
+//   * tokens (B operand, shared by all waves): 18 packed 16x128 tiles = 36 KiB, gathered
+//     through the permutation by asynchronous global->LDS copies (global_load_lds_dwordx4)
+//     into a ring of three LDS images, two K blocks ahead;
+//   * weights (A operand): wave w owns two 16-row tiles of the panel that no other wave
+//     needs, so they bypass LDS: tile-major weights are loaded straight into MFMA operand
+//     registers (contiguous 1 KiB per load) into a ring of three register sets, two K
+//     blocks ahead.
+// LDS capacity bounds how far ahead a workgroup can fetch; staging only the shared operand
+// in LDS halves the bytes per stage, which is what lets both operands run two blocks ahead
+// (with both operands in LDS only one block of lookahead fit and every K block paid the
+// HBM latency: 2.6 us against 1.8 us of compute).
+// Each wave multiplies its 2 weight tiles with all 18 token tiles on
+// v_mfma_f32_16x16x128_f8f6f4 and folds every fp32 partial product into its accumulator with
+// s_act[token,kb] * s_w[nblock,kb] on the VALU.
 //
-// Token tiles of 16 beyond the expert's row count are skipped (not loaded, not
-// multiplied).  Workgroups are numbered so that all weight panels of one M tile run on the
-// same XCD back to back and share the token rows in its L2: block b runs on XCD b % 8 and
-// handles M tile (b/8 / n_panels) * 8 + b % 8, panel (b/8) % n_panels.
+// Synchronisation is explicit: vector-memory operations complete in order, every wave
+// issues the same 10 operations per K block (5 token pieces, 1 scale piece, 4 weight
+// loads; spread between the token tiles of the running multiply), so "everything of block kb has landed" is s_waitcnt vmcnt(10) -- only the 10
+// operations of block kb+1 may still be in flight -- followed by one s_barrier per K block.
+// Past the end of K the ring keeps issuing (clamped to the last block) so the count stays valid.
 //
-// GEMM-1 (G1): rows = 128 gate + 128 up rows of W13, epilogue silu(g)*u, per-token amax
-// over the block's 128 h columns, e4m3 quantisation of h.  GEMM-2: rows = 256 rows of W2,
-// epilogue bf16 store.  Experts with few rows are left to the streaming kernels (they are not listed).
+// Token tiles of 16 beyond the expert's row count are skipped in the multiply.
+// Workgroups are numbered so that all weight panels of one M tile run on the same XCD back
+// to back and share the token rows in its L2: block b runs on XCD b % 8 and handles M tile
+// (b/8 / n_panels) * 8 + b % 8, panel (b/8) % n_panels.
+//
+// GEMM-1 (G1): wave w owns gate tile w and up tile w of the panel (16 h columns), epilogue
+// silu(g)*u, per-token amax over the panel's 128 h columns (LDS, 8 waves), e4m3
+// quantisation of h.  GEMM-2: wave w owns rows 32w..32w+31 of the 256-row panel, bf16 store
+// through an LDS transpose.  Experts with few rows are left to the streaming kernels.
 #include "dwdp_kernels.h"
 
 // Timing experiments only (results are wrong when set): 1 = skip the MFMA/VALU work,
-// 2 = skip the global->LDS copies after the first K block, 4 = skip the weight copies,
-// 8 = skip the token copies.  Never set in a product build.
+// 16 = no per-block wait and barrier, 32 = no LDS operand reads, 64 = no VALU scaling,
+// 128 = no global loads or copies at all, 4 = no weight loads, 8 = no token copies.
+// Never set in a product build.
 #ifndef DWDP_TILE_DBG
 #define DWDP_TILE_DBG 0
 #endif
 
 namespace dwdp {
 
-constexpr int kBM = 288;          // tokens per workgroup tile
-constexpr int kTT = kBM / 16;     // token tiles per workgroup (18)
-constexpr int kWM = 3;            // waves along the token dimension (x 4 along the weight rows)
-constexpr int kTW = (kTT + kWM - 1) / kWM;  // token tiles per wave
-constexpr int kTileWaves = 4 * kWM;
+constexpr int kBM = 288;        // tokens per workgroup tile
+constexpr int kTT = kBM / 16;   // token tiles per workgroup (18)
+constexpr int kTileWaves = 8;
 constexpr int kTileThreads = 64 * kTileWaves;
-constexpr int kLdsA = 16 * kTileBytes;
-constexpr int kLdsB = kTT * kTileBytes;
-constexpr int kSaLen = 320;
-static_assert(kBM <= kSaLen && kTT <= 20, "copy loops cover 40 token half-tiles and 320 scales");
+constexpr int kLdsB = kTT * kTileBytes;  // one token image: 36 KiB
+constexpr int kBPieces = 2 * kTT;        // 1 KiB pieces of a token image
+constexpr int kBP = (kBPieces + kTileWaves - 1) / kTileWaves;  // pieces copied per wave (5)
+constexpr int kSaLen = 64 * kTileWaves;  // scale slots per image: every wave copies 64
+static_assert(kBM <= kSaLen, "one scale slot per token");
+// vector-memory operations per wave and K block, and the wait that proves block kb landed:
+// operations issued after its copies = weights(kb) + all of blocks kb+1's issue
+constexpr int kVmemPerStep = kBP + 1 + 4;
+constexpr int kVmemAfter = kVmemPerStep;  // 10: only block kb+1's operations may still be in flight
+static_assert(kVmemAfter == 10, "the s_waitcnt immediate below assumes 10");
+// s_waitcnt immediate (gfx9 layout): vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14
+#ifndef DWDP_TILE_VMCNT
+#define DWDP_TILE_VMCNT 10
+#endif
+constexpr int kWaitVmStep = (DWDP_TILE_VMCNT & 15) | (7 << 4) | (15 << 8) | ((DWDP_TILE_VMCNT >> 4) << 14);
+constexpr int kWaitVm0 = 0 | (7 << 4) | (15 << 8);
 
 typedef const __attribute__((address_space(1))) v4i* gv4i;
 typedef const __attribute__((address_space(1))) float* gf32;
 // Read-only data addressed with wave-uniform pointers: the constant address space makes
-// these scalar loads (s_load), which do not touch the vector-memory counter the copies use.
+// these scalar loads (s_load), which do not touch the vector-memory counter.
 typedef const __attribute__((address_space(4))) float* cf32;
 
 __device__ __forceinline__ v8i cat8(v4i lo, v4i hi) { return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7); }
@@ -96,16 +119,25 @@ __global__ __launch_bounds__(1024) void build_mtile_list_kernel(const int32_t* _
   if (tid == 1023) *n_mtiles = min(scan_s[1023], cap);
 }
 
-typedef __attribute__((address_space(1))) const void* gvoid;
-typedef __attribute__((address_space(3))) void* lvoid;
-
-// Asynchronous global -> LDS copy of 64 lanes x 16 bytes: lane l's 16 bytes land at dst + l*16.
+// Asynchronous global -> LDS copy of 64 lanes x 16 (or 4) bytes: lane l's bytes land at
+// dst + l*16 (l*4); dst is wave-uniform and goes through M0.  Issued from inline assembly
+// for the same reason as the weight loads below: the compiler must not model these
+// operations, all waiting on them is done with explicit s_waitcnt.
+__device__ __forceinline__ uint32_t lds_offset(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
 __device__ __forceinline__ void dma16(const uint8_t* src_lane, uint8_t* dst_wave_uniform) {
-  __builtin_amdgcn_global_load_lds((gvoid)src_lane, (lvoid)dst_wave_uniform, 16, 0, 0);
+  const uint32_t d = __builtin_amdgcn_readfirstlane(lds_offset(dst_wave_uniform));
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(d), "v"(src_lane) : "memory");
 }
 __device__ __forceinline__ void dma4(const float* src_lane, float* dst_wave_uniform) {
-  __builtin_amdgcn_global_load_lds((gvoid)src_lane, (lvoid)dst_wave_uniform, 4, 0, 0);
+  const uint32_t d = __builtin_amdgcn_readfirstlane(lds_offset(dst_wave_uniform));
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(d), "v"(src_lane) : "memory");
 }
+
+struct AFrag {  // two 16x128 weight tiles in MFMA operand layout (16 registers)
+  v4i t[2][2];
+};
 
 template <bool G1>
 __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
@@ -113,16 +145,16 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
     const int32_t* __restrict__ mt_expert, const int32_t* __restrict__ mt_row0, const int32_t* __restrict__ n_mtiles,
     int n_panels, const uint8_t* __restrict__ act, const float* __restrict__ act_s, uint8_t* __restrict__ hq,
     float* __restrict__ hs, uint16_t* __restrict__ yp, int E, int T, int H, int I, int K) {
-  // Two LDS images (K block kb and kb+1), each its own array so that the compiler can tell
-  // a copy into one from the reads of the other.
-  __shared__ __attribute__((aligned(16))) uint8_t lds_a0[kLdsA];
-  __shared__ __attribute__((aligned(16))) uint8_t lds_a1[kLdsA];
+  // Three token images, each its own array so that the compiler can tell a copy into one
+  // from the reads of another.
   __shared__ __attribute__((aligned(16))) uint8_t lds_b0[kLdsB];
   __shared__ __attribute__((aligned(16))) uint8_t lds_b1[kLdsB];
-  __shared__ __attribute__((aligned(16))) float lds_sa0[kSaLen];  // 5 waves x 64 activation scales
+  __shared__ __attribute__((aligned(16))) uint8_t lds_b2[kLdsB];
+  __shared__ __attribute__((aligned(16))) float lds_sa0[kSaLen];
   __shared__ __attribute__((aligned(16))) float lds_sa1[kSaLen];
-  __shared__ float lds_amax[4 * kBM];
+  __shared__ __attribute__((aligned(16))) float lds_sa2[kSaLen];
   __shared__ int32_t lds_row[kSaLen];
+  __shared__ __attribute__((aligned(16))) uint8_t lds_epi[kTileWaves * kBM * 4];  // amax / store staging
 
   const int xcd = blockIdx.x & 7;
   const int s = blockIdx.x >> 3;
@@ -139,177 +171,220 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   const int ntt = (valid + 15) >> 4;
 
   const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63, lr = lane & 15, lq = lane >> 4;
-  const int wn = wave & 3, wm = wave >> 2;  // wm < kWM
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: pointers derived from it stay in SGPRs
+  const int lane = tid & 63, lr = lane & 15, lq = lane >> 4;
   const int Kdim = G1 ? H : I;  // reduction length
   const int nkb = Kdim / 128;
   const int n_tile_rows = (G1 ? 2 * I : H) / 16;
   const uint8_t* wbase = (const uint8_t*)(G1 ? table[e].w13 : table[e].w2);
   const float* sbase = G1 ? table[e].s13 : table[e].s2;
 
-  // ---- copy sources (fixed over the K loop) ----
-  // weights: 32 pieces of 1 KiB (16 LDS tiles x 2 halves), kAP per wave; LDS tile a = wn*4 + j
-  constexpr int kAP = (32 + kTileWaves - 1) / kTileWaves;
-  const uint8_t* a_src[kAP];
+  // ---- sources, fixed over the K loop ----
+  // weights: this wave's two tiles (G1: gate tile and up tile of 16 h columns; GEMM-2: 32 rows)
+  const uint8_t* a_src[2];
+  const float* sw[2];
 #pragma unroll
-  for (int i = 0; i < kAP; i++) {
-    const int c = min(wave + kTileWaves * i, 31);  // piece: tile c/2, half c&1
-    const int a = c >> 1;
-    const int w = a >> 2, j = a & 3;
+  for (int j = 0; j < 2; j++) {
     int tr;
     if (G1)
-      tr = (j < 2 ? 0 : I / 16) + panel * 8 + 2 * w + (j & 1);
+      tr = (j == 0 ? 0 : I / 16) + panel * 8 + wave;
     else
-      tr = min(panel * 16 + a, n_tile_rows - 1);
-    a_src[i] = wbase + (size_t)tr * nkb * kTileBytes + (c & 1) * (kTileBytes / 2);  // wave-uniform
+      tr = min(panel * 16 + wave * 2 + j, n_tile_rows - 1);
+    a_src[j] = wbase + (size_t)tr * nkb * kTileBytes;  // wave-uniform
+    sw[j] = sbase + (size_t)(tr / 8) * nkb;  // 8 tiles of 16 rows per 128-row scale block
   }
-  // tokens: wave w copies 1 KiB pieces c = w, w+kTileWaves, ... (piece c = token tile c/2, half c&1)
-  // The source row of every token of the tile is kept in LDS (not in registers) and looked
-  // up again by each copy: lds_row[i] = row of act / act_s that token i reads.
-  constexpr int kBP = (2 * kTT + kTileWaves - 1) / kTileWaves;
+  // tokens: the source row of every token slot of the tile (slots past the end repeat the last row)
   for (int i = tid; i < kSaLen; i += kTileThreads) {
     const int row = min(r0 + i, r_end - 1);
     lds_row[i] = G1 ? ((e < E) ? perm[row] / K : row - T * K) : row;
   }
   __syncthreads();
-  // scale rows of this wave's tiles: G1 gate block / up block; GEMM-2 one block per wave pair
-  const float* sw0;
-  const float* sw1;
-  if (G1) {
-    sw0 = sbase + (size_t)panel * nkb;
-    sw1 = sbase + (size_t)(I / 128 + panel) * nkb;
-  } else {
-    const int blk = min(panel * 2 + (wn >> 1), H / 128 - 1);
-    sw0 = sw1 = sbase + (size_t)blk * nkb;
+  // this wave's token pieces: piece c = tile c/2, half c&1; slots past the image repeat piece 35
+  uint32_t b_src[kBP];
+#pragma unroll
+  for (int i = 0; i < kBP; i++) {
+    const int c = min(wave + kTileWaves * i, kBPieces - 1);
+    b_src[i] = (uint32_t)lds_row[(c >> 1) * 16 + lr] * Kdim + lq * 32 + (c & 1) * 16;
   }
+  const float* sa_src = act_s + (size_t)lds_row[wave * 64 + lane] * nkb;
 
-  v4f acc[4][kTW];
+  v4f acc[2][kTT];
 #pragma unroll
-  for (int j = 0; j < 4; j++)
+  for (int j = 0; j < 2; j++)
 #pragma unroll
-    for (int t = 0; t < kTW; t++) acc[j][t] = (v4f){0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < kTT; t++) acc[j][t] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-  auto issue = [&](uint8_t* la, uint8_t* lb, float* lsa, int kb) {
-#pragma unroll
-    for (int i = 0; i < kAP; i++) {
-      const int c = wave + kTileWaves * i;
-      if (c < 32 && !(DWDP_TILE_DBG & 4))
-        dma16(a_src[i] + (size_t)kb * kTileBytes + lane * 16, la + c * (kTileBytes / 2));
+  // Issue everything block kb needs: always exactly kVmemPerStep operations, tokens first.
+  // One of the kVmemPerStep vector-memory operations that fetch block kb: ops 0..kBP-1 copy
+  // token pieces, op kBP the activation scales, the last four load this wave's weights.
+  // The weight loads are issued from inline assembly so that the compiler does not model
+  // them: it cannot order loads that stay in flight across the loop's back edge and would
+  // drain the whole queue before the first MFMA of every block.  Their completion is covered
+  // by the explicit s_waitcnt in publish(); the registers are read-write operands so each
+  // fragment keeps its registers, and nothing reads them between issue and wait.
+  auto issue_op = [&](int op, uint8_t* lb, float* lsa, AFrag& a, int kb) {
+    if (DWDP_TILE_DBG & 128) return;
+    if (op < kBP) {
+      const int c = min(wave + kTileWaves * op, kBPieces - 1);
+      if (!(DWDP_TILE_DBG & 8)) dma16(act + (b_src[op] + (uint32_t)kb * 128), lb + c * (kTileBytes / 2));
+    } else if (op == kBP) {
+      if (!(DWDP_TILE_DBG & 8)) dma4(sa_src + kb, lsa + wave * 64);
+    } else if (!(DWDP_TILE_DBG & 4)) {
+      const int j = (op - kBP - 1) >> 1, half = (op - kBP - 1) & 1;
+      const uint8_t* p = a_src[j] + (size_t)kb * kTileBytes + half * (kTileBytes / 2) + lane * 16;
+      asm volatile("global_load_dwordx4 %0, %1, off nt" : "+v"(a.t[j][half]) : "v"(p));
     }
+  };
+  auto issue = [&](uint8_t* lb, float* lsa, AFrag& a, int kb) {
 #pragma unroll
-    for (int i = 0; i < kBP; i++) {
-      const int c = wave + kTileWaves * i;
-      if (c < 2 * ntt && !(DWDP_TILE_DBG & 8)) {
-        const uint32_t off = (uint32_t)lds_row[(c >> 1) * 16 + lr] * Kdim + lq * 32 + (c & 1) * 16 + kb * 128;
-        dma16(act + off, lb + c * (kTileBytes / 2));
-      }
-    }
-    if (wave < 5) dma4(act_s + (size_t)lds_row[wave * 64 + lane] * nkb + kb, lsa + wave * 64);
+    for (int op = 0; op < kVmemPerStep; op++) issue_op(op, lb, lsa, a, kb);
   };
 
-  auto compute = [&](const uint8_t* la, const uint8_t* lb, const float* lsa, int kb) {
-    const float w0 = *(cf32)(sw0 + kb);
-    const float w1 = *(cf32)(sw1 + kb);
-    // one per-lane base per LDS array; every tile is a compile-time offset from it
-    const uint8_t* pa = la + wn * 4 * kTileBytes + lane * 16;
-    const uint8_t* pb = lb + wm * kTileBytes + lane * 16;
-    const float* ps = lsa + wm * 16 + lr;
-    v8i af[4];
+  // Multiply block kb from (lb, lsa, a) and, spread between its token tiles, issue the
+  // fetches of block kbn into (lbn, lsan, an): issued in one burst the ten operations keep
+  // the wave at the memory pipeline's door for as long as the transfers take, one every
+  // other tile they slip in under the MFMAs.
+  // Token tiles are processed in pairs with two operand buffers (no register copies): while
+  // the MFMAs of tile t run, the LDS reads of tile t+1 are already in flight.
+  auto compute = [&](const uint8_t* lb, const float* lsa, const AFrag& a, int kb, uint8_t* lbn, float* lsan,
+                     AFrag& an, int kbn) {
+    const float w0 = *(cf32)(sw[0] + kb);
+    const float w1 = *(cf32)(sw[1] + kb);
+    const v8i af0 = cat8(a.t[0][0], a.t[0][1]);
+    const v8i af1 = cat8(a.t[1][0], a.t[1][1]);
+    const uint8_t* pb = lb + lane * 16;
+    const float* ps = lsa + lr;
+    const v4f zero = {0.f, 0.f, 0.f, 0.f};
+    v8i bfx, bfy;
+    float sax, say = 0.f;
+    bfx = cat8(*(const v4i*)pb, *(const v4i*)(pb + kTileBytes / 2));
+    sax = ps[0];
+    bfy = bfx;
+    auto tile = [&](int t, const v8i& bf, float sa, v8i& bf_n, float& sa_n) {
+      if (t < ntt && !(DWDP_TILE_DBG & 1)) {
+        if (t + 1 < kTT && !(DWDP_TILE_DBG & 32)) {  // tile t+1 is always inside the LDS image
+          bf_n = cat8(*(const v4i*)(pb + (t + 1) * kTileBytes),
+                      *(const v4i*)(pb + (t + 1) * kTileBytes + kTileBytes / 2));
+          sa_n = ps[(t + 1) * 16];
+        }
+        if (DWDP_TILE_DBG & 64) {
+          acc[0][t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af0, bf, acc[0][t], 0, 0, 0, 0, 0, 0);
+          acc[1][t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af1, bf, acc[1][t], 0, 0, 0, 0, 0, 0);
+        } else {
+          const v4f p0 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af0, bf, zero, 0, 0, 0, 0, 0, 0);
+          const v4f p1 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af1, bf, zero, 0, 0, 0, 0, 0, 0);
+          const float s0 = sa * w0, s1 = sa * w1;
 #pragma unroll
-    for (int j = 0; j < 4; j++)
-      af[j] = cat8(*(const v4i*)(pa + j * kTileBytes), *(const v4i*)(pa + j * kTileBytes + kTileBytes / 2));
+          for (int i = 0; i < 4; i++) acc[0][t][i] = fmaf(p0[i], s0, acc[0][t][i]);
 #pragma unroll
-    for (int ti = 0; ti < kTW; ti++) {
-      const int t = wm + kWM * ti;
-      if (t < ntt) {
-        const uint8_t* p = pb + ti * (kWM * kTileBytes);
-        const v8i bf = cat8(*(const v4i*)p, *(const v4i*)(p + kTileBytes / 2));
-        const float sa = ps[ti * (kWM * 16)];
-        const float s0 = sa * w0, s1 = sa * w1;
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-          const v4f zero = {0.f, 0.f, 0.f, 0.f};
-          const v4f pr = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af[j], bf, zero, 0, 0, 0, 0, 0, 0);
-          const float sj = (j < 2) ? s0 : s1;
-#pragma unroll
-          for (int i = 0; i < 4; i++) acc[j][ti][i] = fmaf(pr[i], sj, acc[j][ti][i]);
+          for (int i = 0; i < 4; i++) acc[1][t][i] = fmaf(p1[i], s1, acc[1][t][i]);
         }
       }
+      // operations 0..8 after tiles 0,2,..,16, operation 9 after tile 17 (always, also past ntt)
+      if ((t & 1) == 0 && t / 2 < kVmemPerStep - 1) issue_op(t / 2, lbn, lsan, an, kbn);
+      if (t == kTT - 1) issue_op(kVmemPerStep - 1, lbn, lsan, an, kbn);
+      __builtin_amdgcn_sched_barrier(0);
+    };
+#pragma unroll
+    for (int t = 0; t < kTT; t += 2) {
+      tile(t, bfx, sax, bfy, say);
+      tile(t + 1, bfy, say, bfx, sax);
     }
   };
+  static_assert(kTT / 2 >= kVmemPerStep - 1 && kTT % 2 == 0, "every operation has a tile to follow");
 
-  // One barrier per K block: it publishes the image copied during the previous block and
-  // retires the reads of the image that the next copy overwrites.
-  issue(lds_a0, lds_b0, lds_sa0, 0);
-  for (int kb = 0; kb < nkb; kb += 2) {
-    __syncthreads();
-    if (kb + 1 < nkb && !(DWDP_TILE_DBG & 2)) issue(lds_a1, lds_b1, lds_sa1, kb + 1);
-    if (!(DWDP_TILE_DBG & 1)) compute(lds_a0, lds_b0, lds_sa0, kb);
+  // "block kb has landed for everyone, and everyone is done with the image that the next
+  // issue overwrites": own copies complete (in-order counter), then one barrier.
+  auto publish = [&]() {
+    if (DWDP_TILE_DBG & 16) return;
+    // pinned between scheduling barriers: nothing of the following issue (its address
+    // arithmetic reuses registers of retired loads) may move above the wait
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(kWaitVmStep);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  AFrag a0 = {}, a1 = {}, a2 = {};
+  issue(lds_b0, lds_sa0, a0, 0);
+  issue(lds_b1, lds_sa1, a1, min(1, nkb - 1));
+  for (int kb = 0; kb < nkb; kb += 3) {
+    publish();
+    compute(lds_b0, lds_sa0, a0, kb, lds_b2, lds_sa2, a2, min(kb + 2, nkb - 1));
     if (kb + 1 < nkb) {
-      __syncthreads();
-      if (kb + 2 < nkb && !(DWDP_TILE_DBG & 2)) issue(lds_a0, lds_b0, lds_sa0, kb + 2);
-      if (!(DWDP_TILE_DBG & 1)) compute(lds_a1, lds_b1, lds_sa1, kb + 1);
+      publish();
+      compute(lds_b1, lds_sa1, a1, kb + 1, lds_b0, lds_sa0, a0, min(kb + 3, nkb - 1));
+    }
+    if (kb + 2 < nkb) {
+      publish();
+      compute(lds_b2, lds_sa2, a2, kb + 2, lds_b1, lds_sa1, a1, min(kb + 4, nkb - 1));
     }
   }
+  // drain the ring's surplus copies before LDS is reused
+  __builtin_amdgcn_s_waitcnt(kWaitVm0);
+  __syncthreads();
 
   if (G1) {
     const int njb = I / 128;
-    // h = silu(gate) * up, kept in acc[0..1]
+    float* lds_amax = (float*)lds_epi;  // [8 waves][kBM]
+    // h = silu(gate) * up, kept in acc[0]
 #pragma unroll
-    for (int ti = 0; ti < kTW; ti++) {
-      const int t = wm + kWM * ti;
+    for (int t = 0; t < kTT; t++) {
       float amax = 0.f;
       if (t < ntt) {
 #pragma unroll
-        for (int j = 0; j < 2; j++)
-#pragma unroll
-          for (int i = 0; i < 4; i++) {
-            const float g = acc[j][ti][i], u = acc[2 + j][ti][i];
-            const float v = g / (1.f + __expf(-g)) * u;
-            acc[j][ti][i] = v;
-            amax = fmaxf(amax, fabsf(v));
-          }
+        for (int i = 0; i < 4; i++) {
+          const float g = acc[0][t][i], u = acc[1][t][i];
+          const float v = g / (1.f + __expf(-g)) * u;
+          acc[0][t][i] = v;
+          amax = fmaxf(amax, fabsf(v));
+        }
       }
       amax = fmaxf(amax, __shfl_xor(amax, 16));
       amax = fmaxf(amax, __shfl_xor(amax, 32));
-      if (lq == 0 && t < kTT) lds_amax[wn * kBM + t * 16 + lr] = amax;
+      if (lq == 0) lds_amax[wave * kBM + t * 16 + lr] = amax;
     }
     __syncthreads();
 #pragma unroll
-    for (int ti = 0; ti < kTW; ti++) {
-      const int t = wm + kWM * ti;
+    for (int t = 0; t < kTT; t++) {
       if (t < ntt) {
         const int tok = t * 16 + lr;
-        const float amax = fmaxf(fmaxf(lds_amax[tok], lds_amax[kBM + tok]),
-                                 fmaxf(lds_amax[2 * kBM + tok], lds_amax[3 * kBM + tok]));
+        float amax = 0.f;
+#pragma unroll
+        for (int w = 0; w < kTileWaves; w++) amax = fmaxf(amax, lds_amax[w * kBM + tok]);
         const float scale = amax > 0.f ? amax / 448.f : 1.f;
         const int r = r0 + tok;
         if (r < r_end) {
-#pragma unroll
-          for (int j = 0; j < 2; j++) {
-            const uint32_t q = pack_fp8x4(acc[j][ti][0] / scale, acc[j][ti][1] / scale, acc[j][ti][2] / scale,
-                                          acc[j][ti][3] / scale);
-            *(uint32_t*)(hq + (size_t)r * I + panel * 128 + wn * 32 + j * 16 + lq * 4) = q;
-          }
-          if (wn == 0 && lq == 0) hs[(size_t)r * njb + panel] = scale;
+          const uint32_t q =
+              pack_fp8x4(acc[0][t][0] / scale, acc[0][t][1] / scale, acc[0][t][2] / scale, acc[0][t][3] / scale);
+          *(uint32_t*)(hq + (size_t)r * I + panel * 128 + wave * 16 + lq * 4) = q;
+          if (wave == 0 && lq == 0) hs[(size_t)r * njb + panel] = scale;
         }
       }
     }
   } else {
+    // bf16 output through LDS: a lane holds 4 consecutive n of ONE token, so direct stores
+    // would be 8-byte pieces scattered over 16 rows; staged per wave as [16 tokens][32 n]
+    // (row pitch 80 B against bank conflicts) a lane stores 16 bytes and 4 lanes cover one
+    // token's 64 contiguous bytes.
+    constexpr int kPitch = 80;
+    uint8_t* stage = lds_epi + wave * (16 * kPitch);
+    const int n_wave = panel * 256 + wave * 32;
+    if (n_wave < H) {
 #pragma unroll
-    for (int j = 0; j < 4; j++) {
-      const int n0 = panel * 256 + (wn * 4 + j) * 16;
-      if (n0 < H) {
+      for (int t = 0; t < kTT; t++) {
+        if (t < ntt) {
 #pragma unroll
-        for (int ti = 0; ti < kTW; ti++) {
-          const int t = wm + kWM * ti;
-          const int r = r0 + t * 16 + lr;
-          if (t < ntt && r < r_end) {
+          for (int j = 0; j < 2; j++) {
             uint2 o;
-            o.x = (uint32_t)f32_to_bf16(acc[j][ti][0]) | ((uint32_t)f32_to_bf16(acc[j][ti][1]) << 16);
-            o.y = (uint32_t)f32_to_bf16(acc[j][ti][2]) | ((uint32_t)f32_to_bf16(acc[j][ti][3]) << 16);
-            *(uint2*)(yp + (size_t)r * H + n0 + lq * 4) = o;
+            o.x = (uint32_t)f32_to_bf16(acc[j][t][0]) | ((uint32_t)f32_to_bf16(acc[j][t][1]) << 16);
+            o.y = (uint32_t)f32_to_bf16(acc[j][t][2]) | ((uint32_t)f32_to_bf16(acc[j][t][3]) << 16);
+            *(uint2*)(stage + lr * kPitch + (j * 16 + lq * 4) * 2) = o;
           }
+          const int tok = lane >> 2, chunk = lane & 3;
+          const v4i v = *(const v4i*)(stage + tok * kPitch + chunk * 16);
+          const int r = r0 + t * 16 + tok;
+          if (r < r_end) *(v4i*)(yp + (size_t)r * H + n_wave + chunk * 8) = v;
         }
       }
     }
