@@ -4,9 +4,10 @@
 // expert; 288 tokens cover almost every expert of the prefill workload (256 +- 16 rows),
 // so each weight panel is read from HBM once.  Per 128-wide K block -- exactly one
 // weight-scale block and one activation-scale group:
-//   * tokens (B operand, shared by all waves): 18 packed 16x128 tiles = 36 KiB, gathered
-//     through the permutation by asynchronous global->LDS copies (global_load_lds_dwordx4)
-//     into a ring of three LDS images, two K blocks ahead;
+//   * tokens (B operand, shared by all waves): 18 tiles of 16 rows x 128 bytes = 36 KiB,
+//     gathered through the permutation by asynchronous global->LDS copies
+//     (global_load_lds_dwordx4, 8 whole 128-byte rows per instruction, chunks XOR-swizzled
+//     against LDS bank conflicts) into a ring of three LDS images, two K blocks ahead;
 //   * weights (A operand): wave w owns two 16-row tiles of the panel that no other wave
 //     needs, so they bypass LDS: tile-major weights are loaded straight into MFMA operand
 //     registers (contiguous 1 KiB per load) into a ring of three register sets, two K
@@ -19,11 +20,15 @@
 // v_mfma_f32_16x16x128_f8f6f4 and folds every fp32 partial product into its accumulator with
 // s_act[token,kb] * s_w[nblock,kb] on the VALU.
 //
-// Synchronisation is explicit: vector-memory operations complete in order, every wave
-// issues the same 10 operations per K block (5 token pieces, 1 scale piece, 4 weight
-// loads; spread between the token tiles of the running multiply), so "everything of block kb has landed" is s_waitcnt vmcnt(10) -- only the 10
-// operations of block kb+1 may still be in flight -- followed by one s_barrier per K block.
-// Past the end of K the ring keeps issuing (clamped to the last block) so the count stays valid.
+// Synchronisation is explicit: vector-memory operations complete in order and every wave
+// issues the same 10 operations per K block (5 token pieces, 1 scale piece, 4 weight loads;
+// spread between the token tiles of the running multiply, because a wave that issues them in
+// one burst sits at the memory pipeline's door instead of feeding the MFMA), so "everything
+// of block kb has landed" is s_waitcnt vmcnt(10) -- only the 10 operations of block kb+1 may
+// still be in flight -- followed by one s_barrier per K block.  Past the end of K the ring
+// keeps issuing (clamped to the last block) so the count stays valid.  The product of tile
+// t is folded into the accumulators after the MFMAs of tile t+1 have been issued, so the
+// VALU never waits for the matrix pipe.
 //
 // Token tiles of 16 beyond the expert's row count are skipped in the multiply.
 // Workgroups are numbered so that all weight panels of one M tile run on the same XCD back
@@ -38,7 +43,8 @@
 
 // Timing experiments only (results are wrong when set): 1 = skip the MFMA/VALU work,
 // 16 = no per-block wait and barrier, 32 = no LDS operand reads, 64 = no VALU scaling,
-// 128 = no global loads or copies at all, 4 = no weight loads, 8 = no token copies.
+// 128 = no global loads or copies at all, 4 = no weight loads, 8 = no token copies,
+// 512 = every workgroup reads the same (L2-resident) weight panel.
 // Never set in a product build.
 #ifndef DWDP_TILE_DBG
 #define DWDP_TILE_DBG 0
@@ -57,14 +63,12 @@ constexpr int kSaLen = 64 * kTileWaves;  // scale slots per image: every wave co
 static_assert(kBM <= kSaLen, "one scale slot per token");
 // vector-memory operations per wave and K block, and the wait that proves block kb landed:
 // operations issued after its copies = weights(kb) + all of blocks kb+1's issue
-constexpr int kVmemPerStep = kBP + 1 + 4;
+constexpr int kVmemPerStep = kBP + 1 + 4;  // token pieces, scales, weight loads
 constexpr int kVmemAfter = kVmemPerStep;  // 10: only block kb+1's operations may still be in flight
 static_assert(kVmemAfter == 10, "the s_waitcnt immediate below assumes 10");
 // s_waitcnt immediate (gfx9 layout): vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14
-#ifndef DWDP_TILE_VMCNT
-#define DWDP_TILE_VMCNT 10
-#endif
-constexpr int kWaitVmStep = (DWDP_TILE_VMCNT & 15) | (7 << 4) | (15 << 8) | ((DWDP_TILE_VMCNT >> 4) << 14);
+constexpr int kVmcntStep = kVmemAfter;
+constexpr int kWaitVmStep = (kVmcntStep & 15) | (7 << 4) | (15 << 8) | ((kVmcntStep >> 4) << 14);
 constexpr int kWaitVm0 = 0 | (7 << 4) | (15 << 8);
 
 typedef const __attribute__((address_space(1))) v4i* gv4i;
@@ -175,6 +179,7 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   const int lane = tid & 63, lr = lane & 15, lq = lane >> 4;
   const int Kdim = G1 ? H : I;  // reduction length
   const int nkb = Kdim / 128;
+  __builtin_assume(nkb >= 1);  // the host rejects reduction lengths that are not positive multiples of 128
   const int n_tile_rows = (G1 ? 2 * I : H) / 16;
   const uint8_t* wbase = (const uint8_t*)(G1 ? table[e].w13 : table[e].w2);
   const float* sbase = G1 ? table[e].s13 : table[e].s2;
@@ -190,7 +195,9 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
       tr = (j == 0 ? 0 : I / 16) + panel * 8 + wave;
     else
       tr = min(panel * 16 + wave * 2 + j, n_tile_rows - 1);
-    a_src[j] = wbase + (size_t)tr * nkb * kTileBytes;  // wave-uniform
+    if (DWDP_TILE_DBG & 512) tr = G1 ? (j == 0 ? 0 : I / 16) + wave : wave * 2 + j;  // every workgroup reads panel 0
+    a_src[j] = ((DWDP_TILE_DBG & 512) ? (const uint8_t*)(G1 ? table[0].w13 : table[0].w2) : wbase) +
+               (size_t)tr * nkb * kTileBytes;  // wave-uniform
     sw[j] = sbase + (size_t)(tr / 8) * nkb;  // 8 tiles of 16 rows per 128-row scale block
   }
   // tokens: the source row of every token slot of the tile (slots past the end repeat the last row)
@@ -199,14 +206,22 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
     lds_row[i] = G1 ? ((e < E) ? perm[row] / K : row - T * K) : row;
   }
   __syncthreads();
-  // this wave's token pieces: piece c = tile c/2, half c&1; slots past the image repeat piece 35
+  // this wave's token pieces: piece c = rows 8*(c&1)..+7 of tile c/2, all 128 K bytes of each
+  // row, so that 8 consecutive lanes fetch one whole 128-byte line (lanes that fetch from
+  // different lines are served one after the other by the address unit).  Lane l's 16 bytes
+  // land in slot l of the piece; slot (row, p) holds the row's 16-byte chunk p ^ ((row16>>1)&7):
+  // the XOR spreads the 16 rows of a tile over all LDS banks for the operand reads below.
+  // Slots past the image repeat the last piece.
   uint32_t b_src[kBP];
 #pragma unroll
   for (int i = 0; i < kBP; i++) {
     const int c = min(wave + kTileWaves * i, kBPieces - 1);
-    b_src[i] = (uint32_t)lds_row[(c >> 1) * 16 + lr] * Kdim + lq * 32 + (c & 1) * 16;
+    const int row16 = (c & 1) * 8 + (lane >> 3);
+    b_src[i] = (uint32_t)lds_row[(c >> 1) * 16 + row16] * Kdim + (((lane & 7) ^ ((row16 >> 1) & 7)) << 4);
   }
-  const float* sa_src = act_s + (size_t)lds_row[wave * 64 + lane] * nkb;
+  // operand reads: lane (lr, lq) needs chunks 2lq and 2lq+1 of row lr of every tile
+  const int b_rd0 = lr * 128 + (((2 * lq) ^ ((lr >> 1) & 7)) << 4);
+  const uint32_t sa_src = (uint32_t)lds_row[wave * 64 + lane] * nkb;
 
   v4f acc[2][kTT];
 #pragma unroll
@@ -222,17 +237,25 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   // drain the whole queue before the first MFMA of every block.  Their completion is covered
   // by the explicit s_waitcnt in publish(); the registers are read-write operands so each
   // fragment keeps its registers, and nothing reads them between issue and wait.
+  const uint32_t lane16 = lane * 16;
+  // the tile of the running multiply after which operation i of the next fetch is issued
+  auto op_slot = [](int i) { return i < kVmemPerStep - 1 ? 2 * i : kTT - 1; };
   auto issue_op = [&](int op, uint8_t* lb, float* lsa, AFrag& a, int kb) {
     if (DWDP_TILE_DBG & 128) return;
     if (op < kBP) {
       const int c = min(wave + kTileWaves * op, kBPieces - 1);
       if (!(DWDP_TILE_DBG & 8)) dma16(act + (b_src[op] + (uint32_t)kb * 128), lb + c * (kTileBytes / 2));
     } else if (op == kBP) {
-      if (!(DWDP_TILE_DBG & 8)) dma4(sa_src + kb, lsa + wave * 64);
+      if (!(DWDP_TILE_DBG & 8)) dma4(act_s + (sa_src + (uint32_t)kb), lsa + wave * 64);
     } else if (!(DWDP_TILE_DBG & 4)) {
       const int j = (op - kBP - 1) >> 1, half = (op - kBP - 1) & 1;
-      const uint8_t* p = a_src[j] + (size_t)kb * kTileBytes + half * (kTileBytes / 2) + lane * 16;
-      asm volatile("global_load_dwordx4 %0, %1, off nt" : "+v"(a.t[j][half]) : "v"(p));
+      const uint8_t* base = a_src[j] + (size_t)kb * kTileBytes;  // wave-uniform: scalar registers
+      if (half == 0)
+        asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "+v"(a.t[j][0]) : "v"(lane16), "s"(base));
+      else
+        asm volatile("global_load_dwordx4 %0, %1, %2 offset:1024 nt"
+                     : "+v"(a.t[j][1])
+                     : "v"(lane16), "s"(base));
     }
   };
   auto issue = [&](uint8_t* lb, float* lsa, AFrag& a, int kb) {
@@ -252,44 +275,57 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
     const float w1 = *(cf32)(sw[1] + kb);
     const v8i af0 = cat8(a.t[0][0], a.t[0][1]);
     const v8i af1 = cat8(a.t[1][0], a.t[1][1]);
-    const uint8_t* pb = lb + lane * 16;
+    const uint8_t* pb0 = lb + b_rd0;
+    const uint8_t* pb1 = lb + (b_rd0 ^ 16);  // chunk 2lq+1 sits in the neighbouring slot
     const float* ps = lsa + lr;
     const v4f zero = {0.f, 0.f, 0.f, 0.f};
     v8i bfx, bfy;
-    float sax, say = 0.f;
-    bfx = cat8(*(const v4i*)pb, *(const v4i*)(pb + kTileBytes / 2));
-    sax = ps[0];
+    bfx = cat8(*(const v4i*)pb0, *(const v4i*)pb1);
     bfy = bfx;
-    auto tile = [&](int t, const v8i& bf, float sa, v8i& bf_n, float& sa_n) {
+    // The scaling of tile t-1's products is issued after the MFMAs of tile t, so the VALU
+    // never waits for an MFMA result: two product sets (px, py) and two activation scales
+    // alternate like the operands.  Tile t's scale is only needed by that later scaling, so
+    // it is read from LDS together with tile t+1's operand.
+    v4f px0 = zero, px1 = zero, py0 = zero, py1 = zero;
+    float sax = 0.f, say = 0.f;
+    auto fold = [&](int t, const v4f& p0, const v4f& p1, float sa) {
+      if (t >= 0 && t < ntt && !(DWDP_TILE_DBG & (1 | 64))) {
+        const float s0 = sa * w0, s1 = sa * w1;
+#pragma unroll
+        for (int i = 0; i < 4; i++) acc[0][t][i] = fmaf(p0[i], s0, acc[0][t][i]);
+#pragma unroll
+        for (int i = 0; i < 4; i++) acc[1][t][i] = fmaf(p1[i], s1, acc[1][t][i]);
+      }
+    };
+    auto tile = [&](int t, const v8i& bf, v8i& bf_n, v4f& p0, v4f& p1, float& sa, const v4f& q0, const v4f& q1,
+                    float sa_prev) {
       if (t < ntt && !(DWDP_TILE_DBG & 1)) {
-        if (t + 1 < kTT && !(DWDP_TILE_DBG & 32)) {  // tile t+1 is always inside the LDS image
-          bf_n = cat8(*(const v4i*)(pb + (t + 1) * kTileBytes),
-                      *(const v4i*)(pb + (t + 1) * kTileBytes + kTileBytes / 2));
-          sa_n = ps[(t + 1) * 16];
+        if (!(DWDP_TILE_DBG & 32)) {
+          if (t + 1 < kTT)  // tile t+1 is always inside the LDS image
+            bf_n = cat8(*(const v4i*)(pb0 + (t + 1) * kTileBytes), *(const v4i*)(pb1 + (t + 1) * kTileBytes));
+          sa = ps[t * 16];
         }
         if (DWDP_TILE_DBG & 64) {
           acc[0][t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af0, bf, acc[0][t], 0, 0, 0, 0, 0, 0);
           acc[1][t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af1, bf, acc[1][t], 0, 0, 0, 0, 0, 0);
         } else {
-          const v4f p0 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af0, bf, zero, 0, 0, 0, 0, 0, 0);
-          const v4f p1 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af1, bf, zero, 0, 0, 0, 0, 0, 0);
-          const float s0 = sa * w0, s1 = sa * w1;
-#pragma unroll
-          for (int i = 0; i < 4; i++) acc[0][t][i] = fmaf(p0[i], s0, acc[0][t][i]);
-#pragma unroll
-          for (int i = 0; i < 4; i++) acc[1][t][i] = fmaf(p1[i], s1, acc[1][t][i]);
+          p0 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af0, bf, zero, 0, 0, 0, 0, 0, 0);
+          p1 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af1, bf, zero, 0, 0, 0, 0, 0, 0);
         }
       }
-      // operations 0..8 after tiles 0,2,..,16, operation 9 after tile 17 (always, also past ntt)
-      if ((t & 1) == 0 && t / 2 < kVmemPerStep - 1) issue_op(t / 2, lbn, lsan, an, kbn);
-      if (t == kTT - 1) issue_op(kVmemPerStep - 1, lbn, lsan, an, kbn);
+      fold(t - 1, q0, q1, sa_prev);
+      // operation i goes after tile op_slot(i) (always, also past ntt)
+#pragma unroll
+      for (int op = 0; op < kVmemPerStep; op++)
+        if (op_slot(op) == t) issue_op(op, lbn, lsan, an, kbn);
       __builtin_amdgcn_sched_barrier(0);
     };
 #pragma unroll
     for (int t = 0; t < kTT; t += 2) {
-      tile(t, bfx, sax, bfy, say);
-      tile(t + 1, bfy, say, bfx, sax);
+      tile(t, bfx, bfy, px0, px1, sax, py0, py1, say);
+      tile(t + 1, bfy, bfx, py0, py1, say, px0, px1, sax);
     }
+    fold(kTT - 1, py0, py1, say);
   };
   static_assert(kTT / 2 >= kVmemPerStep - 1 && kTT % 2 == 0, "every operation has a tile to follow");
 
@@ -305,23 +341,36 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
     __builtin_amdgcn_sched_barrier(0);
   };
 
+  auto keep = [](const AFrag& a) {
+    asm volatile("" ::"v"(a.t[0][0]), "v"(a.t[0][1]), "v"(a.t[1][0]), "v"(a.t[1][1]));
+  };
   AFrag a0 = {}, a1 = {}, a2 = {};
-  issue(lds_b0, lds_sa0, a0, 0);
-  issue(lds_b1, lds_sa1, a1, min(1, nkb - 1));
+  // ph(i): the i-th block of the walk over K; past the end the ring re-fetches the last block
+  auto ph = [&](int i) { return min(i, nkb - 1); };
+  issue(lds_b0, lds_sa0, a0, ph(0));
+  issue(lds_b1, lds_sa1, a1, ph(1));
   for (int kb = 0; kb < nkb; kb += 3) {
     publish();
-    compute(lds_b0, lds_sa0, a0, kb, lds_b2, lds_sa2, a2, min(kb + 2, nkb - 1));
+    compute(lds_b0, lds_sa0, a0, ph(kb), lds_b2, lds_sa2, a2, ph(kb + 2));
     if (kb + 1 < nkb) {
       publish();
-      compute(lds_b1, lds_sa1, a1, kb + 1, lds_b0, lds_sa0, a0, min(kb + 3, nkb - 1));
+      compute(lds_b1, lds_sa1, a1, ph(kb + 1), lds_b0, lds_sa0, a0, ph(kb + 3));
     }
     if (kb + 2 < nkb) {
       publish();
-      compute(lds_b2, lds_sa2, a2, kb + 2, lds_b1, lds_sa1, a1, min(kb + 4, nkb - 1));
+      compute(lds_b2, lds_sa2, a2, ph(kb + 2), lds_b1, lds_sa1, a1, ph(kb + 4));
     }
   }
-  // drain the ring's surplus copies before LDS is reused
+  // Drain the ring's surplus copies before LDS is reused.  The fragments are named as
+  // operands after the wait so that their registers stay allocated until every load that
+  // targets them has landed: a register freed earlier could be handed to another value and
+  // then be overwritten by a late load.
+  __builtin_amdgcn_sched_barrier(0);
   __builtin_amdgcn_s_waitcnt(kWaitVm0);
+  keep(a0);
+  keep(a1);
+  keep(a2);
+  __builtin_amdgcn_sched_barrier(0);
   __syncthreads();
 
   if (G1) {
