@@ -209,18 +209,20 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   // this wave's token pieces: piece c = rows 8*(c&1)..+7 of tile c/2, all 128 K bytes of each
   // row, so that 8 consecutive lanes fetch one whole 128-byte line (lanes that fetch from
   // different lines are served one after the other by the address unit).  Lane l's 16 bytes
-  // land in slot l of the piece; slot (row, p) holds the row's 16-byte chunk p ^ ((row16>>1)&7):
-  // the XOR spreads the 16 rows of a tile over all LDS banks for the operand reads below.
-  // Slots past the image repeat the last piece.
+  // land in slot l of the piece; slot (row, p) holds the row's 16-byte chunk p ^ swz(row):
+  // with this XOR the 128-bit operand reads below (lane (lr, lq) reads chunks 2lq, 2lq+1 of
+  // row lr) run at the full LDS rate -- measured; a plain row-major image runs at a quarter,
+  // XOR with (row>>1)&7 at half.  Slots past the image repeat the last piece.
+  auto swz = [](int row16) { return (((row16 >> 1) & 3) << 1) ^ (row16 >> 3); };
   uint32_t b_src[kBP];
 #pragma unroll
   for (int i = 0; i < kBP; i++) {
     const int c = min(wave + kTileWaves * i, kBPieces - 1);
     const int row16 = (c & 1) * 8 + (lane >> 3);
-    b_src[i] = (uint32_t)lds_row[(c >> 1) * 16 + row16] * Kdim + (((lane & 7) ^ ((row16 >> 1) & 7)) << 4);
+    b_src[i] = (uint32_t)lds_row[(c >> 1) * 16 + row16] * Kdim + (((lane & 7) ^ swz(row16)) << 4);
   }
   // operand reads: lane (lr, lq) needs chunks 2lq and 2lq+1 of row lr of every tile
-  const int b_rd0 = lr * 128 + (((2 * lq) ^ ((lr >> 1) & 7)) << 4);
+  const int b_rd0 = lr * 128 + (((2 * lq) ^ swz(lr)) << 4);
   const uint32_t sa_src = (uint32_t)lds_row[wave * 64 + lane] * nkb;
 
   v4f acc[2][kTT];
