@@ -19,9 +19,11 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 FP8_PEAK_TFLOPS = 5000.0     # MI355X dense FP8 MFMA, published
-# HBM bytes of the dominant kernel from the committed rocprofv3 counter runs (profiles/): keyed by
-# (seed, T) of the decode workload; None when this configuration was not profiled.
-PROFILED_TRAFFIC = {(1, 64): 4651422 * 1024}
+# HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs (profiles/:
+# FETCH_SIZE x 2.0 + WRITE_SIZE, calibrated against a 1 GiB copy), keyed by (workload, seed, T); None
+# when this configuration was not profiled.
+PROFILED_TRAFFIC = {("decode", 1, 64): (2325711 * 2 + 1238) * 1024,
+                    ("prefill", 1, 8192): (4529624 * 2 + 152067) * 1024}
 
 
 def parse():
@@ -165,10 +167,8 @@ def main():
 
     roof = roofline("gemm1", "gemm1_tile", b13, 2 * 2 * cfg.I * cfg.H, "GEMM-1 (gate/up + SwiGLU)")
     roof2 = roofline("gemm2", "gemm2_tile", b2, 2 * cfg.I * cfg.H, "GEMM-2 (down)")
-    if args.workload == "decode" and roof["bound"] == "hbm":
-        # rocprofv3 FETCH_SIZE x 2.0 (calibrated against a 1 GiB copy) for this kernel and workload,
-        # from profiles/decode_T64_stream_gemm.md: bytes per launch
-        roof["traffic"] = PROFILED_TRAFFIC.get((args.seed, cfg.T))
+    if args.stream_max_rows is None:
+        roof["traffic"] = PROFILED_TRAFFIC.get((args.workload, args.seed, cfg.T))
 
     out = {
         "metric": "moe_layer_tokens_per_s", "value": cfg.T / (ms_per_step * 1e-3), "unit": "tokens/s",
