@@ -249,10 +249,12 @@ extern "C" dwdp_status dwdp_permute(dwdp_ctx* ctx, const int32_t* topk_ids, int3
   return DWDP_OK;
 }
 
-// Profiling events per call: kProfMain+1 on the compute stream (route .. end) and 3 on the aux
-// stream (tile GEMM-1 start, tile GEMM-2 start, end).
+// Profiling events per call: route, permute, quant, combine and end on the compute stream; the
+// streaming chain's GEMM-1 start, GEMM-2 start and end on that chain's stream; the tiled chain's
+// GEMM-1 start, GEMM-2 start and end on the compute stream.
 constexpr int kProfMain = 6;
-constexpr int kProfPerCall = kProfMain + 1 + 3;
+constexpr int kProfStreamEnd = kProfMain + 4;  // after the streaming chain's GEMM-2, on that chain's stream
+constexpr int kProfPerCall = kProfMain + 1 + 3 + 1;
 static inline hipEvent_t prof_event(dwdp_ctx* ctx, int idx) {
   return ctx->prof_ev[(size_t)ctx->prof_calls * kProfPerCall + idx];
 }
@@ -297,45 +299,56 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
   const bool use_stream = smr > 0;
   TileSched ts{ctx->mt_expert, ctx->mt_row0, ctx->n_mtiles, 0};
   if (fp8) launch_quant_act(x, T, c.H, (uint8_t*)ctx->ws[DWDP_WS_XQ], (float*)ctx->ws[DWDP_WS_XS], s);
+  // Only the grouped GEMMs read expert weights: the wait for the staged experts goes here.
+  if (consume) HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->staged_ev[layer], 0));
+  const int span = tl_open(ctx, DWDP_SPAN_GEMM, layer, s);
+  // Two independent chains when both kernel families have work.  The tiled chain stays on the
+  // compute stream and is enqueued first: its few, large workgroups need whole CUs, and once
+  // the streaming kernel has filled the chip they would only get one when it drains.  The
+  // streamed chain runs on aux behind a fork event (inheriting the wait above) and is joined
+  // before the combine.
+  const bool two = fp8 && use_tile && use_stream;
+  hipStream_t sc = two ? ctx->aux : s;  // stream of the streaming chain
   if (use_tile) {
+    // before the fork: the streaming chain then starts a cross-queue wait behind the tile kernel
     ts.n_mt_max = tile_mtiles_cap(rows, ctx->n_slots, smr);
     launch_build_mtile_list(off, ctx->n_slots, smr, ts.mt_expert, ts.mt_row0, ts.n_mtiles, ts.n_mt_max, s);
   }
-  // Only the grouped GEMMs read expert weights: the wait for the staged experts goes here.
-  if (consume) HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->staged_ev[layer], 0));
-  if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM1), s));
-  const int span = tl_open(ctx, DWDP_SPAN_GEMM, layer, s);
+  if (two) {
+    HIP_TRY(ctx, hipEventRecord(ctx->fork_ev, s));
+    HIP_TRY(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_ev, 0));
+  }
   if (fp8) {
-    // Two independent chains: streamed experts on the compute stream, tiled experts on aux.
-    hipStream_t ts_stream = (use_tile && use_stream) ? ctx->aux : s;
-    if (use_tile && use_stream) {
-      HIP_TRY(ctx, hipEventRecord(ctx->fork_ev, s));
-      HIP_TRY(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_ev, 0));
+    if (use_stream) {
+      if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM1), sc));
+      launch_gemm1_fp8(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
+                       (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], sc);
+      if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM2), sc));
+      launch_gemm2_fp8(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
+                       ctx->ws[DWDP_WS_YP], sc);
+      if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfStreamEnd), sc));
+      if (two) HIP_TRY(ctx, hipEventRecord(ctx->join_ev, ctx->aux));
+    } else if (prof) {
+      HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM1), s));
+      HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM2), s));
+      HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfStreamEnd), s));
     }
     if (use_tile) {
-      if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfMain + 1), ts_stream));
+      if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfMain + 1), s));
       launch_gemm1_fp8_tile(ga, ts, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
-                            (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], ts_stream);
-      if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfMain + 2), ts_stream));
+                            (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], s);
+      if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfMain + 2), s));
       launch_gemm2_fp8_tile(ga, ts, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
-                            ctx->ws[DWDP_WS_YP], ts_stream);
-      if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfMain + 3), ts_stream));
-      if (use_stream) HIP_TRY(ctx, hipEventRecord(ctx->join_ev, ctx->aux));
+                            ctx->ws[DWDP_WS_YP], s);
+      if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfMain + 3), s));
     }
-    if (use_stream) {
-      launch_gemm1_fp8(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
-                       (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], s);
-      if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM2), s));
-      launch_gemm2_fp8(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
-                       ctx->ws[DWDP_WS_YP], s);
-    } else if (prof) {
-      HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM2), s));
-    }
-    if (use_tile && use_stream) HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->join_ev, 0));
+    if (two) HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->join_ev, 0));
   } else {
+    if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM1), s));
     launch_gemm1_bf16(ga, x, ctx->ws[DWDP_WS_HQ], s);
     if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM2), s));
     launch_gemm2_bf16(ga, ctx->ws[DWDP_WS_HQ], ctx->ws[DWDP_WS_YP], s);
+    if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfStreamEnd), s));
   }
   tl_close(ctx, span, s);
   // The layer's weights have been read once GEMM-2 is done: release the staging buffer here.
@@ -531,7 +544,8 @@ extern "C" dwdp_status dwdp_profile_read(dwdp_ctx* ctx, float* ms_sum, int32_t* 
     const hipEvent_t* ev = &ctx->prof_ev[(size_t)i * kProfPerCall];
     for (int s = 0; s < kProfMain; s++) {
       float ms = 0.f;
-      HIP_TRY(ctx, hipEventElapsedTime(&ms, ev[s], ev[s + 1]));
+      // GEMM-2 ends where the streaming chain ends, not where the combine starts (that is after the join)
+      HIP_TRY(ctx, hipEventElapsedTime(&ms, ev[s], ev[s == DWDP_STAGE_GEMM2 ? kProfStreamEnd : s + 1]));
       ms_sum[s] += ms;
     }
     if (ctx->prof_has_aux[i]) {

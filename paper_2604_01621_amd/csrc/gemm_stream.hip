@@ -108,12 +108,17 @@ __device__ __forceinline__ void stream_mainloop(const uint8_t* const (&wt)[NT], 
 }
 
 // Task = (expert slot e, block jb of 128 h columns): gate rows jb*128.., up rows I + jb*128..
-// Wave w owns h columns jb*128 + w*32 + {0..31}: tiles 0,1 gate, tiles 2,3 up.
-__global__ __launch_bounds__(kStreamThreads, 2) void gemm1_fp8_stream_kernel(
+// Wave w of kG1Waves owns kG1T gate tiles and the kG1T up tiles of the same h columns
+// (h columns jb*128 + w*16*kG1T + ..): tiles 0..kG1T-1 gate, kG1T..2*kG1T-1 up.
+// (8 waves with one tile pair each, or other pipeline depths, measure the same within 3 %)
+constexpr int kG1Waves = 4;
+constexpr int kG1T = 8 / kG1Waves;
+constexpr int kG1Threads = 64 * kG1Waves;
+__global__ __launch_bounds__(kG1Threads, 2) void gemm1_fp8_stream_kernel(
     const dwdp_expert_ptrs* __restrict__ table, const int32_t* __restrict__ offsets, const int32_t* __restrict__ perm,
     const uint8_t* __restrict__ xq, const float* __restrict__ xs, uint8_t* __restrict__ hq, float* __restrict__ hs,
     int E, int T, int H, int I, int K, int max_rows) {
-  __shared__ float amax_s[4][16];
+  __shared__ float amax_s[kG1Waves][16];
   const int njb = I / 128;
   const int e = blockIdx.x / njb;
   const int jb = blockIdx.x - e * njb;
@@ -124,10 +129,10 @@ __global__ __launch_bounds__(kStreamThreads, 2) void gemm1_fp8_stream_kernel(
   const int nkb = H / 128;
   const uint8_t* w13 = (const uint8_t*)table[e].w13;
   const float* s13 = table[e].s13;
-  const uint8_t* wt[4];
+  const uint8_t* wt[2 * kG1T];
 #pragma unroll
-  for (int j = 0; j < 4; j++) {
-    const int tile_row = ((j < 2 ? 0 : I) + jb * 128 + wave * 32 + (j & 1) * 16) / 16;
+  for (int j = 0; j < 2 * kG1T; j++) {
+    const int tile_row = ((j < kG1T ? 0 : I) + jb * 128 + wave * (16 * kG1T) + (j % kG1T) * 16) / 16;
     wt[j] = w13 + (size_t)tile_row * nkb * kTileBytes + lane * 16;
   }
   const float* swp[2] = {s13 + (size_t)jb * nkb, s13 + (size_t)(njb + jb) * nkb};
@@ -138,18 +143,18 @@ __global__ __launch_bounds__(kStreamThreads, 2) void gemm1_fp8_stream_kernel(
     const int tok = (e < E) ? perm[rc] / K : rc - T * K;
     const uint8_t* xrow = xq + (size_t)tok * H + lq * 32;
     const float* xsrow = xs + (size_t)tok * nkb;
-    v4f acc[4];
+    v4f acc[2 * kG1T];
 #pragma unroll
-    for (int j = 0; j < 4; j++) acc[j] = (v4f){0.f, 0.f, 0.f, 0.f};
-    stream_mainloop<4, 2>(wt, swp, xrow, xsrow, nkb, acc);
+    for (int j = 0; j < 2 * kG1T; j++) acc[j] = (v4f){0.f, 0.f, 0.f, 0.f};
+    stream_mainloop<2 * kG1T, 2>(wt, swp, xrow, xsrow, nkb, acc);
 
-    float h[2][4];
+    float h[kG1T][4];
     float amax = 0.f;
 #pragma unroll
-    for (int j = 0; j < 2; j++)
+    for (int j = 0; j < kG1T; j++)
 #pragma unroll
       for (int i = 0; i < 4; i++) {
-        float g = acc[j][i], u = acc[2 + j][i];
+        float g = acc[j][i], u = acc[kG1T + j][i];
         float v = g / (1.f + __expf(-g)) * u;
         h[j][i] = v;
         amax = fmaxf(amax, fabsf(v));
@@ -158,13 +163,14 @@ __global__ __launch_bounds__(kStreamThreads, 2) void gemm1_fp8_stream_kernel(
     amax = fmaxf(amax, __shfl_xor(amax, 32));
     if (lq == 0) amax_s[wave][lr] = amax;
     __syncthreads();
-    amax = fmaxf(fmaxf(amax_s[0][lr], amax_s[1][lr]), fmaxf(amax_s[2][lr], amax_s[3][lr]));
+#pragma unroll
+    for (int w = 0; w < kG1Waves; w++) amax = fmaxf(amax, amax_s[w][lr]);
     const float scale = amax > 0.f ? amax / 448.f : 1.f;
     if (r < r1) {
 #pragma unroll
-      for (int j = 0; j < 2; j++) {
+      for (int j = 0; j < kG1T; j++) {
         uint32_t q = pack_fp8x4(h[j][0] / scale, h[j][1] / scale, h[j][2] / scale, h[j][3] / scale);
-        *(uint32_t*)(hq + (size_t)r * I + jb * 128 + wave * 32 + j * 16 + lq * 4) = q;
+        *(uint32_t*)(hq + (size_t)r * I + jb * 128 + wave * (16 * kG1T) + j * 16 + lq * 4) = q;
       }
       if (wave == 0 && lq == 0) hs[(size_t)r * njb + jb] = scale;
     }
@@ -174,38 +180,147 @@ __global__ __launch_bounds__(kStreamThreads, 2) void gemm1_fp8_stream_kernel(
 
 // Task = (expert slot e, block nb of kG2Rows output rows).  Wave w owns kG2Tiles consecutive
 // 16-row tiles, all inside one 128-row scale block.
-constexpr int kG2Tiles = 2;
-constexpr int kG2Rows = 4 * kG2Tiles * 16;  // rows per workgroup (128)
+//
+// The B operand (16 token rows of h, the same for all four waves) is staged in LDS once per
+// 16-row group instead of being loaded by every wave for every K block: with the MFMA lane
+// mapping such a load touches 16 different lines per instruction and costs the address unit
+// more time than the 1 KiB weight loads it accompanies.  K is staged in chunks of at most
+// kG2ChunkK so that the LDS need does not depend on I.  Layout per K block: 16 rows x 128
+// bytes, 16-byte chunks XOR-swizzled (the pattern of the tile kernel's token image) so that
+// the 128-bit operand reads are free of bank conflicts.
+constexpr int kG2Tiles = 1;
+constexpr int kG2Rows = 4 * kG2Tiles * 16;  // rows per workgroup (64)
+// K blocks per pipeline half in GEMM-2.  One tile per wave with four blocks per half measured
+// best at the decode shape (358 us against 394 us for two tiles and two blocks): the short
+// per-expert streams of GEMM-2 (32 KiB per tile row) profit from more, lighter waves.
+constexpr int kU2 = 4;
+constexpr int kG2ChunkK = 2048;
+constexpr int kG2ChunkKb = kG2ChunkK / 128;
+
+typedef const __attribute__((address_space(4))) float* cf32;
+
+__device__ __forceinline__ int g2_swz(int row16) { return (((row16 >> 1) & 3) << 1) ^ (row16 >> 3); }
+
+struct G2Frag {
+  v4i w[kG2Tiles][2];
+  v4i x[2];
+  float sa;
+  float sw;
+};
+
+// wt[j]: wave-uniform base of packed tile row j; lane16 = lane * 16; xb0/xb1: this lane's two
+// chunk addresses inside K block 0 of the LDS image; kb counts from the chunk start, kbg is
+// the same block in the weight matrix.
+__device__ __forceinline__ void g2_load(G2Frag& f, const uint8_t* const (&wt)[kG2Tiles], uint32_t lane16,
+                                        const float* swp, const uint8_t* xb0, const uint8_t* xb1, const float* xsa,
+                                        int kb, int kbg) {
+#pragma unroll
+  for (int j = 0; j < kG2Tiles; j++) {
+    const uint8_t* p = wt[j] + (size_t)kbg * kTileBytes + lane16;
+    f.w[j][0] = __builtin_nontemporal_load((gv4i)p);
+    f.w[j][1] = __builtin_nontemporal_load((gv4i)(p + kTileBytes / 2));
+  }
+  f.x[0] = *(const v4i*)(xb0 + kb * kTileBytes);
+  f.x[1] = *(const v4i*)(xb1 + kb * kTileBytes);
+  f.sa = xsa[kb * 16];
+  f.sw = *(cf32)(swp + kbg);
+}
+
+__device__ __forceinline__ void g2_mma(const G2Frag& f, v4f (&acc)[kG2Tiles]) {
+  const v8i b = cat(f.x[0], f.x[1]);
+  const float s = f.sa * f.sw;
+#pragma unroll
+  for (int j = 0; j < kG2Tiles; j++) {
+    const v4f zero = {0.f, 0.f, 0.f, 0.f};
+    v4f p = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(cat(f.w[j][0], f.w[j][1]), b, zero, 0, 0, 0, 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 4; i++) acc[j][i] = fmaf(p[i], s, acc[j][i]);
+  }
+}
+
 __global__ __launch_bounds__(kStreamThreads, 2) void gemm2_fp8_stream_kernel(
     const dwdp_expert_ptrs* __restrict__ table, const int32_t* __restrict__ offsets, const uint8_t* __restrict__ hq,
     const float* __restrict__ hs, uint16_t* __restrict__ yp, int H, int I, int max_rows) {
+  __shared__ __attribute__((aligned(16))) uint8_t lds_x[kG2ChunkKb * kTileBytes];  // 32 KiB
+  __shared__ float lds_sa[kG2ChunkKb * 16];
   const int nnb = (H + kG2Rows - 1) / kG2Rows;
   const int e = blockIdx.x / nnb;
   const int nb = blockIdx.x - e * nnb;
   const int r0 = offsets[e];
   const int r1 = offsets[e + 1];
   if (r1 <= r0 || r1 - r0 > max_rows) return;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 15, lq = lane >> 4;
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: weight and scale addresses stay in SGPRs
+  const int lane = tid & 63, lr = lane & 15, lq = lane >> 4;
   const int nkb = I / 128;
+  // H is a multiple of 128, not of 256: the last workgroup's upper waves have no rows; they
+  // still take part in the staging and its barriers
   const int row0 = nb * kG2Rows + wave * (kG2Tiles * 16);  // first output row of this wave
-  if (row0 >= H) return;                                   // H is a multiple of 128, not of 256
+  const bool has_rows = row0 < H;
+  const int tr0 = has_rows ? row0 / 16 : 0;
   const uint8_t* w2 = (const uint8_t*)table[e].w2;
   const float* s2 = table[e].s2;
   const uint8_t* wt[kG2Tiles];
 #pragma unroll
-  for (int j = 0; j < kG2Tiles; j++) wt[j] = w2 + (size_t)(row0 / 16 + j) * nkb * kTileBytes + lane * 16;
-  const float* swp[1] = {s2 + (size_t)(row0 / 128) * nkb};
+  for (int j = 0; j < kG2Tiles; j++) wt[j] = w2 + (size_t)(tr0 + j) * nkb * kTileBytes;
+  const float* swp = s2 + (size_t)(tr0 / 8) * nkb;
+  const uint32_t lane16 = lane * 16;
+  const uint8_t* xb0 = lds_x + lr * 128 + (((2 * lq) ^ g2_swz(lr)) << 4);
+  const uint8_t* xb1 = lds_x + lr * 128 + (((2 * lq + 1) ^ g2_swz(lr)) << 4);
+  const float* xsa = lds_sa + lr;
 
   for (int rt = r0; rt < r1; rt += 16) {
-    const int r = rt + lr;
-    const int rc = min(r, r1 - 1);
-    const uint8_t* xrow = hq + (size_t)rc * I + lq * 32;
-    const float* xsrow = hs + (size_t)rc * nkb;
     v4f acc[kG2Tiles];
 #pragma unroll
     for (int j = 0; j < kG2Tiles; j++) acc[j] = (v4f){0.f, 0.f, 0.f, 0.f};
-    stream_mainloop<kG2Tiles, 1>(wt, swp, xrow, xsrow, nkb, acc);
-    if (r < r1) {
+    for (int kc = 0; kc < nkb; kc += kG2ChunkKb) {
+      const int nkc = min(kG2ChunkKb, nkb - kc);
+      // stage rows rt..rt+15 (rows past the end repeat the last one), K blocks kc..kc+nkc-1
+      __syncthreads();  // the previous chunk's readers are done
+      for (int pidx = tid; pidx < nkc * 128; pidx += kStreamThreads) {
+        const int kb = pidx >> 7, row = (pidx >> 3) & 15, c = pidx & 7;
+        const int rc = min(rt + row, r1 - 1);
+        const v4i v = *(gv4i)(hq + (size_t)rc * I + (size_t)(kc + kb) * 128 + c * 16);
+        *(v4i*)(lds_x + kb * kTileBytes + row * 128 + ((c ^ g2_swz(row)) << 4)) = v;
+      }
+      if (tid < nkc * 16) {
+        const int kb = tid >> 4, row = tid & 15;
+        lds_sa[kb * 16 + row] = hs[(size_t)min(rt + row, r1 - 1) * nkb + kc + kb];
+      }
+      __syncthreads();
+      if (has_rows) {
+        // two K blocks of weight loads in flight behind the MFMAs of the previous two
+        constexpr int kStep = 2 * kU2;
+        const int nmain = (nkc / kStep) * kStep;
+        if (nmain > 0) {
+          G2Frag f0[kU2], f1[kU2];
+#pragma unroll
+          for (int u = 0; u < kU2; u++) g2_load(f0[u], wt, lane16, swp, xb0, xb1, xsa, u, kc + u);
+          for (int kb0 = 0; kb0 < nmain; kb0 += kStep) {
+#pragma unroll
+            for (int u = 0; u < kU2; u++)
+              g2_load(f1[u], wt, lane16, swp, xb0, xb1, xsa, kb0 + kU2 + u, kc + kb0 + kU2 + u);
+#pragma unroll
+            for (int u = 0; u < kU2; u++) g2_mma(f0[u], acc);
+            // the last round re-reads the chunk's last block instead of running past it; unused
+#pragma unroll
+            for (int u = 0; u < kU2; u++) {
+              const int kn = min(kb0 + kStep + u, nkc - 1);
+              g2_load(f0[u], wt, lane16, swp, xb0, xb1, xsa, kn, kc + kn);
+            }
+#pragma unroll
+            for (int u = 0; u < kU2; u++) g2_mma(f1[u], acc);
+          }
+        }
+        for (int kb = nmain; kb < nkc; kb++) {
+          G2Frag f;
+          g2_load(f, wt, lane16, swp, xb0, xb1, xsa, kb, kc + kb);
+          g2_mma(f, acc);
+        }
+      }
+    }
+    const int r = rt + lr;
+    if (has_rows && r < r1) {
 #pragma unroll
       for (int j = 0; j < kG2Tiles; j++) {
         uint2 o;
@@ -221,7 +336,7 @@ void launch_gemm1_fp8(const GemmArgs& a, int max_rows, const uint8_t* xq, const 
                       hipStream_t stream) {
   if (a.T <= 0) return;
   dim3 grid(a.n_slots * (a.I / 128));
-  hipLaunchKernelGGL(gemm1_fp8_stream_kernel, grid, dim3(kStreamThreads), 0, stream, a.table, a.offsets, a.perm, xq,
+  hipLaunchKernelGGL(gemm1_fp8_stream_kernel, grid, dim3(kG1Threads), 0, stream, a.table, a.offsets, a.perm, xq,
                      xs, hq, hs, a.E, a.T, a.H, a.I, a.K, max_rows);
 }
 
