@@ -192,10 +192,13 @@ def test_layer_small_fp8(binding, T, smr):
 
 
 @pytest.mark.parametrize("smr", [0, 1 << 30])
-@pytest.mark.parametrize("H,I,T", [(1536, 1024, 37), (1408, 640, 20), (640, 384, 300)])
+@pytest.mark.parametrize("H,I,T", [(1536, 1024, 37), (1408, 640, 20), (640, 384, 300), (256, 2304, 20),
+                                   (384, 1536, 33)])
 def test_layer_fp8_long_k(binding, H, I, T, smr):
-    """K loops of several pipeline rounds plus a remainder (H/128 = 12, 11 or 5; I/128 = 8, 5
-    or 3), output rows not a multiple of the 256-row workgroup tile, on both kernel families."""
+    """K loops of several pipeline rounds plus a remainder (H/128 = 12, 11, 5, 2 or 3; I/128 = 8,
+    5, 3, 18 or 12: the streaming GEMM-2 stages its operand in chunks of 16 K blocks, so 18 runs
+    two chunks), output rows not a multiple of the 256-row workgroup tile, on both kernel
+    families."""
     print("layer fp8 long-k", H, I, T, smr, flush=True)
     cfg = inputs.small_fp8_layer(T=T, H=H, I=I, E=8, K=2, n_group=1, topk_group=1)
     x = inputs.make_activations(cfg, 21)
