@@ -157,9 +157,12 @@ def main():
         compute_bound = tile and rows_tile / max(n_tile, 1) >= 128
         if compute_bound:
             ach = rows_tile * flops_per_row / (t * 1e-3) / 1e12
+            # the same launch against the HBM roofline: every listed expert's weights read once
+            hbm = n_tile * bytes_per_expert / (t * 1e-3) / 1e9
             return {"bound": "mfma", "kernel": kern, "achieved": ach, "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": ach / FP8_PEAK_TFLOPS, "traffic": None,
-                    "algorithmic_flops_per_launch": rows_tile * flops_per_row, "avg_launch_ms": t}
+                    "algorithmic_flops_per_launch": rows_tile * flops_per_row, "avg_launch_ms": t,
+                    "hbm_read_once_gbs": hbm, "hbm_frac": hbm / HBM_PEAK_GBS}
         ach = n_exp * bytes_per_expert / (t * 1e-3) / 1e9
         return {"bound": "hbm", "kernel": kern, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": ach / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_launch": n_exp * bytes_per_expert,

@@ -244,7 +244,7 @@ extern "C" dwdp_status dwdp_permute(dwdp_ctx* ctx, const int32_t* topk_ids, int3
   if (!expert_offsets) return fail(ctx, DWDP_EINVAL, "dwdp_permute: expert_offsets is NULL");
   if (T > 0 && (!topk_ids || !perm || !inv_perm)) return fail(ctx, DWDP_EINVAL, "dwdp_permute: NULL pointer");
   launch_permute(topk_ids, T, ctx->cfg.E, ctx->cfg.K, ctx->cfg.has_shared, ctx->chunk_counts, expert_offsets, perm,
-                 inv_perm, ctx->compute);
+                 inv_perm, nullptr, 0, ctx->compute);
   HIP_TRY(ctx, hipGetLastError());
   return DWDP_OK;
 }
@@ -285,11 +285,6 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
   int32_t* perm = (int32_t*)ctx->ws[DWDP_WS_PERM];
   int32_t* inv = (int32_t*)ctx->ws[DWDP_WS_INV_PERM];
 
-  if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_ROUTE), s));
-  launch_route(logits, c.score_fn == DWDP_SCORE_SIGMOID ? bias : nullptr, T, route_params(c), ids, tw, s);
-  if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_PERMUTE), s));
-  launch_permute(ids, T, c.E, c.K, c.has_shared, ctx->chunk_counts, off, perm, inv, s);
-  if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_QUANT), s));
   GemmArgs ga{table, off, perm, ctx->n_slots, c.E, T, c.H, c.I, c.K};
   const bool fp8 = c.w_dtype == DWDP_W_FP8;
   // Experts with 1..smr rows stream their weights; the others go through the LDS-tiled kernel.
@@ -298,7 +293,20 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
   const bool use_tile = fp8 && T > smr;  // an expert holds at most T rows
   const bool use_stream = smr > 0;
   TileSched ts{ctx->mt_expert, ctx->mt_row0, ctx->n_mtiles, 0};
-  if (fp8) launch_quant_act(x, T, c.H, (uint8_t*)ctx->ws[DWDP_WS_XQ], (float*)ctx->ws[DWDP_WS_XS], s);
+  if (use_tile) ts.n_mt_max = tile_mtiles_cap(rows, ctx->n_slots, smr);
+  // Two launches prepare the GEMMs: routing with the (independent) activation quantisation
+  // riding along as extra workgroups, and the permutation, whose last single-workgroup step
+  // also lists the M tiles of the tiled experts.
+  if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_ROUTE), s));
+  const float* rbias = c.score_fn == DWDP_SCORE_SIGMOID ? bias : nullptr;
+  if (fp8)
+    launch_route_quant(logits, rbias, T, route_params(c), ids, tw, x, c.H, (uint8_t*)ctx->ws[DWDP_WS_XQ],
+                       (float*)ctx->ws[DWDP_WS_XS], s);
+  else
+    launch_route(logits, rbias, T, route_params(c), ids, tw, s);
+  if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_PERMUTE), s));
+  launch_permute(ids, T, c.E, c.K, c.has_shared, ctx->chunk_counts, off, perm, inv, use_tile ? &ts : nullptr, smr, s);
+  if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_QUANT), s));
   // Only the grouped GEMMs read expert weights: the wait for the staged experts goes here.
   if (consume) HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->staged_ev[layer], 0));
   const int span = tl_open(ctx, DWDP_SPAN_GEMM, layer, s);
@@ -309,11 +317,6 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
   // before the combine.
   const bool two = fp8 && use_tile && use_stream;
   hipStream_t sc = two ? ctx->aux : s;  // stream of the streaming chain
-  if (use_tile) {
-    // before the fork: the streaming chain then starts a cross-queue wait behind the tile kernel
-    ts.n_mt_max = tile_mtiles_cap(rows, ctx->n_slots, smr);
-    launch_build_mtile_list(off, ctx->n_slots, smr, ts.mt_expert, ts.mt_row0, ts.n_mtiles, ts.n_mt_max, s);
-  }
   if (two) {
     HIP_TRY(ctx, hipEventRecord(ctx->fork_ev, s));
     HIP_TRY(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_ev, 0));

@@ -27,10 +27,28 @@ int permute_chunk_tokens(int E);
 
 void launch_route(const float* logits, const float* bias, int T, const RouteParams& p, int32_t* ids, float* w,
                   hipStream_t stream);
+// The same routing plus, in the same launch (extra workgroups), the activation quantisation
+// x bf16 [T,H] -> xq fp8 [T,H], xs fp32 [T,H/128]: the two are independent, one launch less.
+void launch_route_quant(const float* logits, const float* bias, int T, const RouteParams& p, int32_t* ids, float* w,
+                        const void* x, int H, uint8_t* xq, float* xs, hipStream_t stream);
 
-// chunk_counts: int32 [n_chunks * E] scratch.
+// Device-built list of the M tiles (up to kTileM sorted rows of one expert) the LDS-tiled GEMM works on.
+constexpr int kTileM = 288;
+struct TileSched {
+  int32_t* mt_expert;  // [n_mt_max] expert slot of the tile
+  int32_t* mt_row0;    // [n_mt_max] first sorted row
+  int32_t* n_mtiles;   // [1] tiles listed
+  int n_mt_max;        // host-side upper bound used to size the grid
+};
+// Upper bound of listed tiles when experts with more than stream_max_rows rows are listed.
+int tile_mtiles_cap(int rows, int n_slots, int stream_max_rows);
+
+// chunk_counts: int32 [n_chunks * E] scratch.  With `list` non-null the single workgroup that
+// finishes the offsets also lists the M tiles of all experts with more than stream_max_rows
+// rows (list->n_mt_max is the capacity of the arrays).
 void launch_permute(const int32_t* ids, int T, int E, int K, int has_shared, int32_t* chunk_counts,
-                    int32_t* offsets, int32_t* perm, int32_t* inv_perm, hipStream_t stream);
+                    int32_t* offsets, int32_t* perm, int32_t* inv_perm, const TileSched* list, int stream_max_rows,
+                    hipStream_t stream);
 
 // x bf16 [T,H] -> xq fp8 [T,H], xs fp32 [T,H/128]
 void launch_quant_act(const void* x, int T, int H, uint8_t* xq, float* xs, hipStream_t stream);
@@ -54,18 +72,6 @@ struct GemmArgs {
   const int32_t* perm;            // device, T*K
   int n_slots, E, T, H, I, K;
 };
-
-// Device-built list of the M tiles (up to 320 sorted rows of one expert) the LDS-tiled GEMM works on.
-struct TileSched {
-  int32_t* mt_expert;  // [n_mt_max] expert slot of the tile
-  int32_t* mt_row0;    // [n_mt_max] first sorted row
-  int32_t* n_mtiles;   // [1] tiles listed
-  int n_mt_max;        // host-side upper bound used to size the grid
-};
-// Upper bound of listed tiles when experts with more than stream_max_rows rows are listed.
-int tile_mtiles_cap(int rows, int n_slots, int stream_max_rows);
-void launch_build_mtile_list(const int32_t* offsets, int n_slots, int stream_max_rows, int32_t* mt_expert,
-                             int32_t* mt_row0, int32_t* n_mtiles, int cap, hipStream_t stream);
 
 // Row-major fp8 [rows, cols] (rows % 16 == 0, cols % 128 == 0) -> tile-major layout of the FP8 GEMMs.
 void launch_pack_fp8_tiles(const void* src, void* dst, long rows, int cols, hipStream_t stream);
@@ -106,6 +112,82 @@ __device__ __forceinline__ uint32_t pack_fp8x4(float a, float b, float c, float 
   v = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, v, false);
   v = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, v, true);
   return (uint32_t)v;
+}
+
+// Quantises 128-element groups of x: 16 lanes own one group (8 bf16 each); `gidx` is this
+// thread's global index over n_groups * 16 lanes.
+__device__ __forceinline__ void quant_act_lane(const uint16_t* __restrict__ x, long n_groups, uint8_t* __restrict__ xq,
+                                               float* __restrict__ xs, long gidx) {
+  long g = gidx >> 4;
+  const int sub = (int)(gidx & 15);
+  const bool live = g < n_groups;
+  if (!live) g = n_groups - 1;  // keep the 16-lane reductions convergent
+  const v4i raw = *(const v4i*)(x + g * 128 + sub * 8);
+  float v[8];
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    uint32_t u = (uint32_t)raw[i];
+    v[2 * i] = __uint_as_float(u << 16);
+    v[2 * i + 1] = __uint_as_float(u & 0xFFFF0000u);
+  }
+  float amax = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; i++) amax = fmaxf(amax, fabsf(v[i]));
+#pragma unroll
+  for (int off = 8; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+  const float scale = amax > 0.f ? amax / 448.f : 1.f;
+  uint32_t lo = pack_fp8x4(v[0] / scale, v[1] / scale, v[2] / scale, v[3] / scale);
+  uint32_t hi = pack_fp8x4(v[4] / scale, v[5] / scale, v[6] / scale, v[7] / scale);
+  if (live) {
+    uint2 o;
+    o.x = lo;
+    o.y = hi;
+    *(uint2*)(xq + g * 128 + sub * 8) = o;
+    if (sub == 0) xs[g] = scale;
+  }
+}
+
+// Lists the M tiles (kTileM rows each) of all experts that have more than stream_max_rows rows.
+// Called by ONE workgroup of 1024 threads after it has written offsets[0..n_slots] (global
+// memory; a __syncthreads separates the writes from this call); thread i owns expert slots
+// 2i and 2i+1, an exclusive block scan of the tile counts gives every expert its place in
+// the list.  scan_s: 1024 ints of LDS.
+__device__ __forceinline__ void build_mtile_list_block(const int32_t* offsets, int n_slots, int stream_max_rows,
+                                                       int32_t* __restrict__ mt_expert, int32_t* __restrict__ mt_row0,
+                                                       int32_t* __restrict__ n_mtiles, int cap, int32_t* scan_s) {
+  const int tid = threadIdx.x;
+  int cnt[2], r0[2];
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+    const int e = 2 * tid + i;
+    cnt[i] = 0;
+    r0[i] = 0;
+    if (e < n_slots) {
+      r0[i] = offsets[e];
+      const int m = offsets[e + 1] - r0[i];
+      if (m > stream_max_rows) cnt[i] = (m + kTileM - 1) / kTileM;
+    }
+  }
+  __syncthreads();  // scan_s may still be in use by the caller's own scan
+  scan_s[tid] = cnt[0] + cnt[1];
+  __syncthreads();
+  for (int d = 1; d < 1024; d <<= 1) {
+    const int v = (tid >= d) ? scan_s[tid - d] : 0;
+    __syncthreads();
+    scan_s[tid] += v;
+    __syncthreads();
+  }
+  int pos = scan_s[tid] - (cnt[0] + cnt[1]);  // exclusive prefix
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+    for (int k = 0; k < cnt[i]; k++, pos++) {
+      if (pos < cap) {
+        mt_expert[pos] = 2 * tid + i;
+        mt_row0[pos] = r0[i] + k * kTileM;
+      }
+    }
+  }
+  if (tid == 1023) *n_mtiles = min(scan_s[1023], cap);
 }
 
 }  // namespace dwdp

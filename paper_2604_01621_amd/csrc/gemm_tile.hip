@@ -52,7 +52,7 @@
 
 namespace dwdp {
 
-constexpr int kBM = 288;        // tokens per workgroup tile
+constexpr int kBM = kTileM;     // tokens per workgroup tile (288)
 constexpr int kTT = kBM / 16;   // token tiles per workgroup (18)
 constexpr int kTileWaves = 8;
 constexpr int kTileThreads = 64 * kTileWaves;
@@ -78,50 +78,6 @@ typedef const __attribute__((address_space(1))) float* gf32;
 typedef const __attribute__((address_space(4))) float* cf32;
 
 __device__ __forceinline__ v8i cat8(v4i lo, v4i hi) { return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7); }
-
-// Lists the M tiles (kBM rows each) of all experts that have more than stream_max_rows rows.
-// One block; thread i owns expert slots 2i and 2i+1, an exclusive block scan of the tile
-// counts gives every expert its place in the list.
-__global__ __launch_bounds__(1024) void build_mtile_list_kernel(const int32_t* __restrict__ offsets, int n_slots,
-                                                                int stream_max_rows,
-                                                                int32_t* __restrict__ mt_expert,
-                                                                int32_t* __restrict__ mt_row0,
-                                                                int32_t* __restrict__ n_mtiles, int cap) {
-  __shared__ int32_t scan_s[1024];
-  const int tid = threadIdx.x;
-  int cnt[2], r0[2], r1[2];
-#pragma unroll
-  for (int i = 0; i < 2; i++) {
-    const int e = 2 * tid + i;
-    cnt[i] = 0;
-    r0[i] = r1[i] = 0;
-    if (e < n_slots) {
-      r0[i] = offsets[e];
-      r1[i] = offsets[e + 1];
-      const int m = r1[i] - r0[i];
-      if (m > stream_max_rows) cnt[i] = (m + kBM - 1) / kBM;
-    }
-  }
-  scan_s[tid] = cnt[0] + cnt[1];
-  __syncthreads();
-  for (int d = 1; d < 1024; d <<= 1) {
-    const int v = (tid >= d) ? scan_s[tid - d] : 0;
-    __syncthreads();
-    scan_s[tid] += v;
-    __syncthreads();
-  }
-  int pos = scan_s[tid] - (cnt[0] + cnt[1]);  // exclusive prefix
-#pragma unroll
-  for (int i = 0; i < 2; i++) {
-    for (int k = 0; k < cnt[i]; k++, pos++) {
-      if (pos < cap) {
-        mt_expert[pos] = 2 * tid + i;
-        mt_row0[pos] = r0[i] + k * kBM;
-      }
-    }
-  }
-  if (tid == 1023) *n_mtiles = min(scan_s[1023], cap);
-}
 
 // Asynchronous global -> LDS copy of 64 lanes x 16 (or 4) bytes: lane l's bytes land at
 // dst + l*16 (l*4); dst is wave-uniform and goes through M0.  Issued from inline assembly
@@ -447,12 +403,6 @@ int tile_mtiles_cap(int rows, int n_slots, int stream_max_rows) {
   // them, each adding at most one partial tile to the rows / kBM full ones
   long by_rows = (long)rows / ((long)stream_max_rows + 1);
   return rows / kBM + (int)(by_rows < n_slots ? by_rows : n_slots) + 1;
-}
-
-void launch_build_mtile_list(const int32_t* offsets, int n_slots, int stream_max_rows, int32_t* mt_expert,
-                             int32_t* mt_row0, int32_t* n_mtiles, int cap, hipStream_t stream) {
-  hipLaunchKernelGGL(build_mtile_list_kernel, dim3(1), dim3(1024), 0, stream, offsets, n_slots, stream_max_rows,
-                     mt_expert, mt_row0, n_mtiles, cap);
 }
 
 void launch_gemm1_fp8_tile(const GemmArgs& a, const TileSched& ts, const uint8_t* xq, const float* xs, uint8_t* hq,

@@ -5,36 +5,9 @@
 
 namespace dwdp {
 
-// 16 lanes own one 128-element group (8 bf16 each); a wave handles 4 groups per step.
 __global__ __launch_bounds__(256) void quant_act_kernel(const uint16_t* __restrict__ x, long n_groups,
                                                         uint8_t* __restrict__ xq, float* __restrict__ xs) {
-  long g = ((long)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
-  const int sub = threadIdx.x & 15;
-  const bool live = g < n_groups;
-  if (!live) g = n_groups - 1;  // keep the 16-lane reductions convergent
-  const v4i raw = *(const v4i*)(x + g * 128 + sub * 8);
-  float v[8];
-#pragma unroll
-  for (int i = 0; i < 4; i++) {
-    uint32_t u = (uint32_t)raw[i];
-    v[2 * i] = __uint_as_float(u << 16);
-    v[2 * i + 1] = __uint_as_float(u & 0xFFFF0000u);
-  }
-  float amax = 0.f;
-#pragma unroll
-  for (int i = 0; i < 8; i++) amax = fmaxf(amax, fabsf(v[i]));
-#pragma unroll
-  for (int off = 8; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
-  const float scale = amax > 0.f ? amax / 448.f : 1.f;
-  uint32_t lo = pack_fp8x4(v[0] / scale, v[1] / scale, v[2] / scale, v[3] / scale);
-  uint32_t hi = pack_fp8x4(v[4] / scale, v[5] / scale, v[6] / scale, v[7] / scale);
-  if (live) {
-    uint2 o;
-    o.x = lo;
-    o.y = hi;
-    *(uint2*)(xq + g * 128 + sub * 8) = o;
-    if (sub == 0) xs[g] = scale;
-  }
+  quant_act_lane(x, n_groups, xq, xs, (long)blockIdx.x * blockDim.x + threadIdx.x);
 }
 
 void launch_quant_act(const void* x, int T, int H, uint8_t* xq, float* xs, hipStream_t stream) {

@@ -20,14 +20,12 @@ __device__ __forceinline__ bool better(float v, int i, float v2, int i2) {
   return v > v2 || (v == v2 && i < i2);
 }
 
-__global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(const float* __restrict__ logits,
-                                                                   const float* __restrict__ bias, int T,
-                                                                   RouteParams p, int32_t* __restrict__ ids,
-                                                                   float* __restrict__ wout) {
-  extern __shared__ float smem[];
+__device__ __forceinline__ void route_block(const float* __restrict__ logits, const float* __restrict__ bias, int T,
+                                            const RouteParams& p, int32_t* __restrict__ ids,
+                                            float* __restrict__ wout, float* smem, int block) {
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  const int t_raw = blockIdx.x * kRouteWaves + wave;
+  const int t_raw = block * kRouteWaves + wave;
   const bool live = t_raw < T;
   const int t = live ? t_raw : T - 1;  // surplus waves redo the last token and write nothing
   const int E = p.E;
@@ -123,12 +121,43 @@ __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(const float* 
   }
 }
 
+__global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(const float* __restrict__ logits,
+                                                                   const float* __restrict__ bias, int T,
+                                                                   RouteParams p, int32_t* __restrict__ ids,
+                                                                   float* __restrict__ wout) {
+  extern __shared__ float smem[];
+  route_block(logits, bias, T, p, ids, wout, smem, blockIdx.x);
+}
+
+// Workgroups [0, n_route) route 4 tokens each, the others quantise 16 groups of 128 activations each.
+__global__ __launch_bounds__(kRouteWaves* kWave) void route_quant_kernel(
+    const float* __restrict__ logits, const float* __restrict__ bias, int T, RouteParams p, int32_t* __restrict__ ids,
+    float* __restrict__ wout, int n_route, const uint16_t* __restrict__ x, long n_groups, uint8_t* __restrict__ xq,
+    float* __restrict__ xs) {
+  extern __shared__ float smem[];
+  if ((int)blockIdx.x < n_route)
+    route_block(logits, bias, T, p, ids, wout, smem, blockIdx.x);
+  else
+    quant_act_lane(x, n_groups, xq, xs, (long)(blockIdx.x - n_route) * blockDim.x + threadIdx.x);
+}
+
 void launch_route(const float* logits, const float* bias, int T, const RouteParams& p, int32_t* ids, float* w,
                   hipStream_t stream) {
   if (T <= 0) return;
   dim3 grid((T + kRouteWaves - 1) / kRouteWaves);
   size_t lds = (size_t)kRouteWaves * (2 * p.E + 128) * sizeof(float);
   hipLaunchKernelGGL(route_kernel, grid, dim3(kRouteWaves * kWave), lds, stream, logits, bias, T, p, ids, w);
+}
+
+void launch_route_quant(const float* logits, const float* bias, int T, const RouteParams& p, int32_t* ids, float* w,
+                        const void* x, int H, uint8_t* xq, float* xs, hipStream_t stream) {
+  if (T <= 0) return;
+  const int n_route = (T + kRouteWaves - 1) / kRouteWaves;
+  const long n_groups = (long)T * (H / kBlockScale);
+  const long n_quant = (n_groups * 16 + kRouteWaves * kWave - 1) / (kRouteWaves * kWave);
+  size_t lds = (size_t)kRouteWaves * (2 * p.E + 128) * sizeof(float);
+  hipLaunchKernelGGL(route_quant_kernel, dim3((unsigned)(n_route + n_quant)), dim3(kRouteWaves * kWave), lds, stream,
+                     logits, bias, T, p, ids, w, n_route, (const uint16_t*)x, n_groups, xq, xs);
 }
 
 // ----------------------------------------------------------------------------- permute
@@ -184,7 +213,8 @@ __global__ __launch_bounds__(kPermThreads) void permute_single_kernel(const int3
                                                                        int K, int has_shared, int wpe,
                                                                        int32_t* __restrict__ offsets,
                                                                        int32_t* __restrict__ perm,
-                                                                       int32_t* __restrict__ inv_perm) {
+                                                                       int32_t* __restrict__ inv_perm, TileSched list,
+                                                                       int stream_max_rows) {
   extern __shared__ uint32_t lds[];
   uint32_t* mask = lds;
   int32_t* scan_s = (int32_t*)(lds + E * wpe);
@@ -203,6 +233,11 @@ __global__ __launch_bounds__(kPermThreads) void permute_single_kernel(const int3
     int r = off_s[e] + rank_in_chunk(mask, e, i / K, wpe);
     perm[r] = i;
     inv_perm[i] = r;
+  }
+  if (list.mt_expert) {
+    __syncthreads();  // offsets[] above were written by other threads of this workgroup
+    build_mtile_list_block(offsets, E + (has_shared ? 1 : 0), stream_max_rows, list.mt_expert, list.mt_row0,
+                           list.n_mtiles, list.n_mt_max, scan_s);
   }
 }
 
@@ -223,7 +258,8 @@ __global__ __launch_bounds__(kPermThreads) void permute_count_kernel(const int32
 // One block: chunk_counts -> exclusive chunk bases (in place), offsets.
 __global__ __launch_bounds__(kPermThreads) void permute_scan_kernel(int32_t* __restrict__ chunk_counts, int n_chunks,
                                                                      int T, int E, int K, int has_shared,
-                                                                     int32_t* __restrict__ offsets) {
+                                                                     int32_t* __restrict__ offsets, TileSched list,
+                                                                     int stream_max_rows) {
   __shared__ int32_t scan_s[kPermThreads];
   int e = threadIdx.x;
   int run = 0;
@@ -236,6 +272,11 @@ __global__ __launch_bounds__(kPermThreads) void permute_scan_kernel(int32_t* __r
   }
   block_scan_offsets(run, E, scan_s, offsets);
   if (has_shared && threadIdx.x == 0) offsets[E + 1] = T * K + T;
+  if (list.mt_expert) {
+    __syncthreads();
+    build_mtile_list_block(offsets, E + (has_shared ? 1 : 0), stream_max_rows, list.mt_expert, list.mt_row0,
+                           list.n_mtiles, list.n_mt_max, scan_s);
+  }
 }
 
 __global__ __launch_bounds__(kPermThreads) void permute_scatter_kernel(const int32_t* __restrict__ ids, int T, int E,
@@ -264,7 +305,9 @@ __global__ void permute_empty_kernel(int32_t* offsets, int n) {
 }
 
 void launch_permute(const int32_t* ids, int T, int E, int K, int has_shared, int32_t* chunk_counts, int32_t* offsets,
-                    int32_t* perm, int32_t* inv_perm, hipStream_t stream) {
+                    int32_t* perm, int32_t* inv_perm, const TileSched* list_in, int stream_max_rows,
+                    hipStream_t stream) {
+  const TileSched list = list_in ? *list_in : TileSched{nullptr, nullptr, nullptr, 0};
   const int n_off = E + 1 + (has_shared ? 1 : 0);
   if (T <= 0) {
     hipLaunchKernelGGL(permute_empty_kernel, dim3((n_off + 255) / 256), dim3(256), 0, stream, offsets, n_off);
@@ -276,14 +319,14 @@ void launch_permute(const int32_t* ids, int T, int E, int K, int has_shared, int
   if (T <= chunk) {
     size_t lds = mask_bytes + (kPermThreads + E + 1) * sizeof(int32_t);
     hipLaunchKernelGGL(permute_single_kernel, dim3(1), dim3(kPermThreads), lds, stream, ids, T, E, K, has_shared, wpe,
-                       offsets, perm, inv_perm);
+                       offsets, perm, inv_perm, list, stream_max_rows);
     return;
   }
   const int n_chunks = (T + chunk - 1) / chunk;
   hipLaunchKernelGGL(permute_count_kernel, dim3(n_chunks), dim3(kPermThreads), mask_bytes, stream, ids, T, E, K, chunk,
                      wpe, chunk_counts);
   hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(kPermThreads), 0, stream, chunk_counts, n_chunks, T, E, K,
-                     has_shared, offsets);
+                     has_shared, offsets, list, stream_max_rows);
   hipLaunchKernelGGL(permute_scatter_kernel, dim3(n_chunks), dim3(kPermThreads), mask_bytes, stream, ids, T, E, K,
                      chunk, wpe, chunk_counts, offsets, perm, inv_perm);
 }
