@@ -149,8 +149,9 @@ dwdp_status dwdp_prefetch_layer(dwdp_ctx* ctx, int32_t layer, const void* const*
 
 /*
  * Kernel selection of the FP8 grouped GEMM.  Experts with 1..max_rows sorted rows are
- * computed by the weight-streaming kernels (no LDS, one 16-token tile at a time), experts
- * with more rows by the LDS-tiled kernels (128-token tiles).  Default 16.  0 sends every
+ * computed by the weight-streaming kernels (weights straight to registers, 16 token rows per
+ * pass over the weights), experts with more rows by the LDS-tiled kernels (288-token tiles,
+ * weights read once per tile).  Default 16.  0 sends every
  * expert to the tiled kernels; a value >= T_max sends every expert to the streaming
  * kernels.  Results are the same function either way (accumulation order differs).
  */
