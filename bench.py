@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--copy-engine", type=int, default=1, help="pipeline workload: 0 hipMemcpyAsync per slice, "
                                                                "1 copy-plan kernel")
     ap.add_argument("--copy-wgs", type=int, default=512, help="pipeline workload: workgroups of the copy-plan kernel")
+    ap.add_argument("--merge-baseline", action="store_true",
+                    help="pipeline workload: merge resident and staged experts into one contiguous image before "
+                         "every layer (the naive split-weight baseline) instead of reading them in place")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="after the timed region run one plain device copy of this many MiB (a known-size "
                          "reference dispatch for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")

@@ -202,8 +202,12 @@ dwdp_status dwdp_build_copy_plan(const void* const* src, void* const* dst, const
  * the compute stream and write the table of the merged copy to merged_table (DEVICE).
  * w13_out/w2_out/s13_out/s2_out hold n_slots experts back to back.
  * table_host is the HOST copy of `table` (the library cannot read device memory on the host).
+ * `layer` names the layer the table belongs to: when a dwdp_prefetch_layer of it is pending,
+ * the copies wait for the staged experts; the staging buffer still belongs to the layer until
+ * its dwdp_moe_forward (called with the merged table) has run.  Experts that already lie
+ * back to back in the source are moved with one copy.
  */
-dwdp_status dwdp_merge_experts(dwdp_ctx* ctx, const dwdp_expert_ptrs* table_host, int32_t n_slots,
+dwdp_status dwdp_merge_experts(dwdp_ctx* ctx, int32_t layer, const dwdp_expert_ptrs* table_host, int32_t n_slots,
                                void* w13_out, float* s13_out, void* w2_out, float* s2_out,
                                dwdp_expert_ptrs* merged_table_host);
 

@@ -57,7 +57,7 @@ def _load() -> C.CDLL:
     lib.dwdp_prefetch_layer.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(sz), i32, i32, sz]
     lib.dwdp_build_copy_plan.argtypes = [C.POINTER(vp), C.POINTER(vp), C.POINTER(sz), i32, i32, sz,
                                          C.POINTER(vp), C.POINTER(vp), C.POINTER(sz), sz, C.POINTER(sz)]
-    lib.dwdp_merge_experts.argtypes = [vp, C.POINTER(dwdp_expert_ptrs), i32, vp, vp, vp, vp,
+    lib.dwdp_merge_experts.argtypes = [vp, i32, C.POINTER(dwdp_expert_ptrs), i32, vp, vp, vp, vp,
                                        C.POINTER(dwdp_expert_ptrs)]
     lib.dwdp_set_stream_max_rows.argtypes = [vp, i32]
     lib.dwdp_set_copy_engine.argtypes = [vp, i32, i32]
@@ -161,13 +161,14 @@ class Context:
         a_b = (sz * max(n_params, 1))(*nbytes)
         self._check(lib.dwdp_prefetch_layer(self.h, layer, a_src, a_dst, a_b, n_peers, n_params, slice_bytes))
 
-    def dwdp_merge_experts(self, table_host: torch.Tensor, w13_out, s13_out, w2_out, s2_out) -> torch.Tensor:
+    def dwdp_merge_experts(self, layer: int, table_host: torch.Tensor, w13_out, s13_out, w2_out,
+                           s2_out) -> torch.Tensor:
         n = table_host.shape[0]
         assert table_host.device.type == "cpu" and table_host.dtype == torch.int64 and table_host.is_contiguous()
         src = C.cast(table_host.data_ptr(), C.POINTER(dwdp_expert_ptrs))
         merged = torch.zeros(n, 4, dtype=torch.int64)
         dst = C.cast(merged.data_ptr(), C.POINTER(dwdp_expert_ptrs))
-        self._check(lib.dwdp_merge_experts(self.h, src, n, _ptr(w13_out), _ptr(s13_out), _ptr(w2_out), _ptr(s2_out),
+        self._check(lib.dwdp_merge_experts(self.h, layer, src, n, _ptr(w13_out), _ptr(s13_out), _ptr(w2_out), _ptr(s2_out),
                                            dst))
         return merged
 

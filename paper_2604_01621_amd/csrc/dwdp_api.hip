@@ -419,7 +419,7 @@ extern "C" dwdp_status dwdp_prefetch_layer(dwdp_ctx* ctx, int32_t layer, const v
   dwdp_build_copy_plan(src, dst, bytes, n_peers, n_params, slice_bytes, pd.data(), ps.data(), pb.data(), n, &n);
   // double buffering: the buffer is free once its previous reader has finished
   if (ctx->done_valid[b]) HIP_TRY(ctx, hipStreamWaitEvent(ctx->copy, ctx->done_ev[b], 0));
-  if (ctx->copy_mode == 1) {
+  if (ctx->copy_mode == DWDP_COPY_KERNEL) {
     // The plan of a layer is static (same regions every iteration): build its device copy once.
     std::vector<uintptr_t> key;
     key.push_back((uintptr_t)n_peers);
@@ -453,7 +453,7 @@ extern "C" dwdp_status dwdp_prefetch_layer(dwdp_ctx* ctx, int32_t layer, const v
     }
   }
   const int span = tl_open(ctx, DWDP_SPAN_COPY, layer, ctx->copy);
-  if (ctx->copy_mode == 1) {
+  if (ctx->copy_mode == DWDP_COPY_KERNEL) {
     launch_copy_plan(ctx->plan_cache[layer].units, ctx->plan_cache[layer].n_units, ctx->copy_wgs, ctx->copy);
     HIP_TRY(ctx, hipGetLastError());
   } else {
@@ -466,29 +466,49 @@ extern "C" dwdp_status dwdp_prefetch_layer(dwdp_ctx* ctx, int32_t layer, const v
   return DWDP_OK;
 }
 
-extern "C" dwdp_status dwdp_merge_experts(dwdp_ctx* ctx, const dwdp_expert_ptrs* table_host, int32_t n_slots,
-                                          void* w13_out, float* s13_out, void* w2_out, float* s2_out,
-                                          dwdp_expert_ptrs* merged_table_host) {
+extern "C" dwdp_status dwdp_merge_experts(dwdp_ctx* ctx, int32_t layer, const dwdp_expert_ptrs* table_host,
+                                          int32_t n_slots, void* w13_out, float* s13_out, void* w2_out,
+                                          float* s2_out, dwdp_expert_ptrs* merged_table_host) {
   if (!ctx) return DWDP_EINVAL;
   if (!table_host || !merged_table_host || !w13_out || !w2_out || n_slots < 0)
     return fail(ctx, DWDP_EINVAL, "dwdp_merge_experts: NULL pointer");
   const dwdp_config& c = ctx->cfg;
+  if (layer < 0 || layer >= c.n_layers) return fail(ctx, DWDP_EINVAL, "layer %d outside [0,%d)", layer, c.n_layers);
   const bool fp8 = c.w_dtype == DWDP_W_FP8;
   if (fp8 && (!s13_out || !s2_out)) return fail(ctx, DWDP_EINVAL, "dwdp_merge_experts: scale outputs are NULL");
+  // a pending prefetch of this layer: the merge reads the staged experts, so it waits for them
+  // (the buffer stays the layer's until its dwdp_moe_forward has run)
+  if (ctx->pending_layer[layer & 1] == layer) HIP_TRY(ctx, hipStreamWaitEvent(ctx->compute, ctx->staged_ev[layer], 0));
   const size_t el = fp8 ? 1 : 2;
   const size_t b13 = (size_t)2 * c.I * c.H * el, b2 = (size_t)c.H * c.I * el;
-  const size_t n13 = (size_t)(2 * c.I / 128) * (c.H / 128), n2 = (size_t)(c.H / 128) * (c.I / 128);
+  const size_t n13 = (size_t)(2 * c.I / 128) * (c.H / 128) * 4, n2 = (size_t)(c.H / 128) * (c.I / 128) * 4;
+  // one copy per run of experts that already lie back to back in the source (a resident
+  // shard, one peer's staged shard): the merged image is the same, the call count is not
+  auto field = [&](int e, int which) -> const char* {
+    const dwdp_expert_ptrs& t = table_host[e];
+    return (const char*)(which == 0 ? t.w13 : which == 1 ? (const void*)t.s13 : which == 2 ? t.w2 : (const void*)t.s2);
+  };
+  char* const outs[4] = {(char*)w13_out, (char*)s13_out, (char*)w2_out, (char*)s2_out};
+  const size_t sizes[4] = {b13, n13, b2, n2};
+  for (int which = 0; which < 4; which++) {
+    if (!fp8 && (which & 1)) continue;  // no scales
+    const size_t bytes = sizes[which];
+    int e = 0;
+    while (e < n_slots) {
+      int f = e + 1;
+      while (f < n_slots && field(f, which) == field(e, which) + (size_t)(f - e) * bytes) f++;
+      HIP_TRY(ctx, hipMemcpyAsync(outs[which] + (size_t)e * bytes, field(e, which), (size_t)(f - e) * bytes,
+                                  hipMemcpyDeviceToDevice, ctx->compute));
+      e = f;
+    }
+  }
   for (int e = 0; e < n_slots; e++) {
     dwdp_expert_ptrs m{};
-    m.w13 = (char*)w13_out + e * b13;
-    m.w2 = (char*)w2_out + e * b2;
-    HIP_TRY(ctx, hipMemcpyAsync((void*)m.w13, table_host[e].w13, b13, hipMemcpyDeviceToDevice, ctx->compute));
-    HIP_TRY(ctx, hipMemcpyAsync((void*)m.w2, table_host[e].w2, b2, hipMemcpyDeviceToDevice, ctx->compute));
+    m.w13 = outs[0] + (size_t)e * b13;
+    m.w2 = outs[2] + (size_t)e * b2;
     if (fp8) {
-      m.s13 = s13_out + e * n13;
-      m.s2 = s2_out + e * n2;
-      HIP_TRY(ctx, hipMemcpyAsync((void*)m.s13, table_host[e].s13, n13 * 4, hipMemcpyDeviceToDevice, ctx->compute));
-      HIP_TRY(ctx, hipMemcpyAsync((void*)m.s2, table_host[e].s2, n2 * 4, hipMemcpyDeviceToDevice, ctx->compute));
+      m.s13 = (const float*)(outs[1] + (size_t)e * n13);
+      m.s2 = (const float*)(outs[3] + (size_t)e * n2);
     }
     merged_table_host[e] = m;
   }

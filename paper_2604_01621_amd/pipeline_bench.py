@@ -54,6 +54,26 @@ def run(args):
         ys.append(torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device=dev))
     torch.cuda.synchronize()
 
+    merge = bool(getattr(args, "merge_baseline", False))
+    if merge:
+        # naive baseline of paper Section 4.2: before each layer's GEMMs, copy its resident and staged
+        # experts into one contiguous image and run the same kernels on that
+        n = cfg.n_slots
+        m_w13 = torch.empty(n, 2 * cfg.I, cfg.H, dtype=torch.uint8, device=dev)
+        m_s13 = torch.empty(n, 2 * cfg.I // 128, cfg.H // 128, dtype=torch.float32, device=dev)
+        m_w2 = torch.empty(n, cfg.H, cfg.I, dtype=torch.uint8, device=dev)
+        m_s2 = torch.empty(n, cfg.H // 128, cfg.I // 128, dtype=torch.float32, device=dev)
+        tables_host = [t.cpu().contiguous() for t in layers.tables]
+        merged_dev = ctx.dwdp_merge_experts(0, tables_host[0], m_w13, m_s13, m_w2, m_s2).to(dev)   # same for all layers
+        torch.cuda.synchronize()
+
+    def forward(l):
+        if merge:
+            ctx.dwdp_merge_experts(l, tables_host[l], m_w13, m_s13, m_w2, m_s2)
+            ctx.dwdp_moe_forward(l, xs[l], lgs[l], bs[l], merged_dev, ys[l])
+        else:
+            ctx.dwdp_moe_forward(l, xs[l], lgs[l], bs[l], layers.tables[l], ys[l])
+
     def loop(n_iter, with_prefetch=True):
         # steady state: the prefetch of the next iteration's layer 0 runs under this iteration's last layer
         for it in range(n_iter):
@@ -62,7 +82,7 @@ def run(args):
                     nxt = (l + 1) % n_layers
                     if not (it == n_iter - 1 and l == n_layers - 1):
                         layers.prefetch(ctx, nxt, slice_bytes)
-                ctx.dwdp_moe_forward(l, xs[l], lgs[l], bs[l], layers.tables[l], ys[l])
+                forward(l)
 
     # compute alone (staging already holds valid experts after one warm pass) and copy alone
     layers.prefetch(ctx, 0, slice_bytes)
@@ -113,6 +133,8 @@ def run(args):
         "config": {"workload": "pipeline: 4 DeepSeek-R1-shaped MoE layers, 64 resident + 192 staged experts each",
                    "T": cfg.T, "layers": n_layers, "slice_bytes": slice_bytes, "active_expert_slots": active,
                    "copy_engine": "copy-plan kernel, %d workgroups" % copy_wgs if engine == 1 else "hipMemcpyAsync per slice",
+                   "split_weights": "merged into one contiguous image before every layer (naive baseline)" if merge
+                   else "read in place through the expert-pointer table",
                    "prefetch_bytes_per_layer": pf_bytes},
         "ms_per_layer": ms_per_layer, "compute_alone_ms_per_layer": compute_alone_ms,
         "copy_alone_ms_per_layer": copy_alone_ms, "copy_alone_gbs": pf_bytes / (copy_alone_ms * 1e-3) / 1e9,

@@ -138,9 +138,46 @@ def test_merged_copy_equals_mixed_table(env):
     w2 = torch.empty(n, cfg.H, cfg.I, dtype=torch.uint8, device="cuda")
     s13 = torch.empty(n, 2 * cfg.I // 128, cfg.H // 128, device="cuda")
     s2 = torch.empty(n, cfg.H // 128, cfg.I // 128, device="cuda")
-    merged = ctx.dwdp_merge_experts(layers.tables[l].cpu().contiguous(), w13, s13, w2, s2)
+    merged = ctx.dwdp_merge_experts(l, layers.tables[l].cpu().contiguous(), w13, s13, w2, s2)
     y_merged = torch.empty_like(y_mixed)
     ctx.dwdp_moe_forward(l, xs[l], lgs[l], bs[l], merged.cuda(), y_merged)
     torch.cuda.synchronize()
     assert merged[1, 0] - merged[0, 0] == 2 * cfg.I * cfg.H            # contiguous
     np.testing.assert_array_equal(y_merged.float().cpu().numpy(), y_mixed.float().cpu().numpy())
+
+
+def test_non_divisible_group_with_redundant_experts(gpu_device):
+    """A DWDP group whose size does not divide the expert count (paper Section 2, last
+    paragraphs): 16 experts over 3 ranks -> every rank keeps 6 (neighbouring ranks overlap in
+    one expert) and pulls 5 from each of its 2 peers.  Only the pointer table and the prefetch
+    lists change; results must equal the all-in-place reference bit for bit."""
+    from paper_2604_01621_amd import binding, pipeline
+    print("non-divisible placement", flush=True)
+    cfg = inputs.small_fp8_layer(T=40)
+    n_layers, n_res, n_peers = 2, 6, 2
+    ctx = binding.Context(cfg, n_layers=n_layers)
+    layers = pipeline.SplitWeightLayers(ctx, cfg, n_layers, n_res, n_peers, seed=300)
+    assert layers.per == 5 and layers.ranges == [(6, 11), (11, 16)]
+    eb = inputs.expert_bytes(cfg)
+    assert layers.prefetch_bytes() == 10 * eb          # 10 of 16 experts pulled per layer, 6 + shared resident
+    ctx.dwdp_set_copy_engine(1, 16)
+    for b in range(2):
+        layers.poison_staging(b)
+    ys, refs = [], []
+    for l in range(n_layers):
+        x = inputs.make_activations(cfg, 310 + l).cuda()
+        lg = inputs.make_gate_logits(cfg, x.cpu(), 310 + l).cuda()
+        y = torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device="cuda")
+        ref = torch.empty_like(y)
+        layers.prefetch(ctx, l, 3000)
+        ctx.dwdp_moe_forward(l, x, lg, None, layers.tables[l], y)
+        ctx.dwdp_moe_forward(l, x, lg, None, layers.all_resident_table(l), ref)
+        ys.append(y)
+        refs.append(ref)
+    torch.cuda.synchronize()
+    ctx.dwdp_set_copy_engine(0)
+    for l in range(n_layers):
+        got = ys[l].float().cpu().numpy()
+        assert np.isfinite(got).all()
+        np.testing.assert_array_equal(got, refs[l].float().cpu().numpy())
+    ctx.close()
