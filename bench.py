@@ -35,7 +35,8 @@ def parse():
     ap.add_argument("--T", type=int, default=None, help="override the workload's token count")
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=2)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=16,
+                    help="tokens of the workload the CPU oracle is timed on (about 10-20 s of host work at 16)")
     ap.add_argument("--slice-mib", type=int, default=1, help="pipeline workload: prefetch slice size in MiB")
     ap.add_argument("--stream-max-rows", type=int, default=None,
                     help="override the library's kernel-selection threshold (dwdp_set_stream_max_rows)")
