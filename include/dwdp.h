@@ -13,7 +13,9 @@
  *     library never frees caller memory; it allocates its own workspace in dwdp_create.
  *   - Calls enqueue work on the context's compute stream (or its private copy stream for
  *     dwdp_prefetch_layer) and return without waiting.  Buffers must stay valid until
- *     the stream has passed the call.
+ *     the stream has passed the call.  dwdp_moe_forward may run part of its grouped GEMM
+ *     on a second private stream; that work is forked from and joined back into the
+ *     compute stream with events, so callers only ever order against the compute stream.
  *   - Errors are return codes; argument errors are detected on the host before anything
  *     is enqueued.  dwdp_last_error() gives a message for the last failure on a context.
  *   - Not thread-safe per context; use one context per host thread.
