@@ -110,8 +110,11 @@ def expert_table(weights: ExpertWeights, device=None) -> torch.Tensor:
     for e in range(weights.n):
         rows.append([weights.w13[e].data_ptr(), weights.s13[e].data_ptr() if weights.s13 is not None else 0,
                      weights.w2[e].data_ptr(), weights.s2[e].data_ptr() if weights.s2 is not None else 0])
-    t = torch.tensor(rows, dtype=torch.int64)
-    return t.to(device if device is not None else weights.w13.device)
+    t = torch.tensor(rows, dtype=torch.int64).to(device if device is not None else weights.w13.device)
+    # The table holds raw addresses.  It keeps the tensors they point into alive, so that
+    # expert_table(ctx.pack_experts(w)) does not leave it pointing at freed (and soon reused) memory.
+    t._dwdp_keepalive = weights
+    return t
 
 
 class Context:

@@ -60,6 +60,10 @@ constexpr int kLdsB = kTT * kTileBytes;  // one token image: 36 KiB
 constexpr int kBPieces = 2 * kTT;        // 1 KiB pieces of a token image
 constexpr int kBP = (kBPieces + kTileWaves - 1) / kTileWaves;  // pieces copied per wave (5)
 constexpr int kSaLen = 64 * kTileWaves;  // scale slots per image: every wave copies 64
+// epilogue scratch: GEMM-1 keeps one amax per (wave, token), GEMM-2 stages 16 tokens x 80 bytes per wave
+constexpr int kStagePitch = 80;
+constexpr int kEpiBytes =
+    kTileWaves * kBM * 4 > kTileWaves * 16 * kStagePitch ? kTileWaves * kBM * 4 : kTileWaves * 16 * kStagePitch;
 static_assert(kBM <= kSaLen, "one scale slot per token");
 // vector-memory operations per wave and K block, and the wait that proves block kb landed:
 // operations issued after its copies = weights(kb) + all of blocks kb+1's issue
@@ -114,7 +118,7 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   __shared__ __attribute__((aligned(16))) float lds_sa1[kSaLen];
   __shared__ __attribute__((aligned(16))) float lds_sa2[kSaLen];
   __shared__ int32_t lds_row[kSaLen];
-  __shared__ __attribute__((aligned(16))) uint8_t lds_epi[kTileWaves * kBM * 4];  // amax / store staging
+  __shared__ __attribute__((aligned(16))) uint8_t lds_epi[kEpiBytes];  // amax / store staging
 
   const int xcd = blockIdx.x & 7;
   const int s = blockIdx.x >> 3;
@@ -374,7 +378,7 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
     // would be 8-byte pieces scattered over 16 rows; staged per wave as [16 tokens][32 n]
     // (row pitch 80 B against bank conflicts) a lane stores 16 bytes and 4 lanes cover one
     // token's 64 contiguous bytes.
-    constexpr int kPitch = 80;
+    constexpr int kPitch = kStagePitch;
     uint8_t* stage = lds_epi + wave * (16 * kPitch);
     const int n_wave = panel * 256 + wave * 32;
     if (n_wave < H) {

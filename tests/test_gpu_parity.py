@@ -137,7 +137,8 @@ def _layer_case(binding, cfg, x, logits, bias, w, check_intermediates=False, str
     ctx = binding.Context(cfg)
     if stream_max_rows is not None:
         ctx.dwdp_set_stream_max_rows(stream_max_rows)
-    table = binding.expert_table(ctx.pack_experts(wd))
+    wp = ctx.pack_experts(wd)              # stays referenced: the table below holds raw addresses into it
+    table = binding.expert_table(wp)
     xd, ld = x.to(dev), logits.to(dev)
     bd = None if bias is None else bias.to(dev)
     y = gpu_forward(ctx, cfg, xd, ld, bd, table)
@@ -218,7 +219,8 @@ def test_layer_small_fp8_no_shared_and_empty(binding):
     ctx = binding.Context(cfg)
     wd = inputs.ExpertWeights(w.w13.cuda(), w.w2.cuda(), w.s13.cuda(), w.s2.cuda())
     y = torch.empty(0, cfg.H, dtype=torch.bfloat16, device="cuda")
-    ctx.dwdp_moe_forward(0, x[:0].cuda(), logits[:0].cuda(), None, binding.expert_table(ctx.pack_experts(wd)), y)
+    wp = ctx.pack_experts(wd)
+    ctx.dwdp_moe_forward(0, x[:0].cuda(), logits[:0].cuda(), None, binding.expert_table(wp), y)
     torch.cuda.synchronize()
     ctx.close()
 
