@@ -132,9 +132,10 @@ extern "C" dwdp_status dwdp_create(const dwdp_config* cfg, void* compute_stream,
   bytes[DWDP_WS_PERM] = T * K * 4;
   bytes[DWDP_WS_INV_PERM] = T * K * 4;
   bytes[DWDP_WS_XQ] = fp8 ? T * H : 0;
-  bytes[DWDP_WS_XS] = fp8 ? T * (H / 128) * 4 : 0;
+  // + 16: the tiled GEMM copies a row's scales three K blocks at a time and may read two floats past the last row
+  bytes[DWDP_WS_XS] = fp8 ? T * (H / 128) * 4 + 16 : 0;
   bytes[DWDP_WS_HQ] = c->rows_max * I * (fp8 ? 1 : 4);
-  bytes[DWDP_WS_HS] = fp8 ? c->rows_max * (I / 128) * 4 : 0;
+  bytes[DWDP_WS_HS] = fp8 ? c->rows_max * (I / 128) * 4 + 16 : 0;
   bytes[DWDP_WS_YP] = c->rows_max * H * (fp8 ? 2 : 4);
   hipError_t e = hipGetDevice(&c->device);
   for (int i = 0; i < DWDP_N_WS && e == hipSuccess; i++)

@@ -21,11 +21,12 @@
 // s_act[token,kb] * s_w[nblock,kb] on the VALU.
 //
 // Synchronisation is explicit: vector-memory operations complete in order and every wave
-// issues the same 10 operations per K block (5 token pieces, 1 scale piece, 4 weight loads;
+// issues the same operations per K block (5 token pieces, 4 weight loads, every third block a scale copy;
 // spread between the token tiles of the running multiply, because a wave that issues them in
 // one burst sits at the memory pipeline's door instead of feeding the MFMA), so "everything
-// of block kb has landed" is s_waitcnt vmcnt(10) -- only the 10 operations of block kb+1 may
-// still be in flight -- followed by one s_barrier per K block.  Past the end of K the ring
+// of block kb has landed" is s_waitcnt vmcnt(n) with n = the operations of block kb+1 (9, or
+// 10 when it carries a scale copy) -- only those may still be in flight -- followed by one
+// s_barrier per K block.  Past the end of K the ring
 // keeps issuing (clamped to the last block) so the count stays valid.  The product of tile
 // t is folded into the accumulators after the MFMAs of tile t+1 have been issued, so the
 // VALU never waits for the matrix pipe.
@@ -39,6 +40,8 @@
 // silu(g)*u, per-token amax over the panel's 128 h columns (LDS, 8 waves), e4m3
 // quantisation of h.  GEMM-2: wave w owns rows 32w..32w+31 of the 256-row panel, bf16 store
 // through an LDS transpose.  Experts with few rows are left to the streaming kernels.
+#include <type_traits>
+
 #include "dwdp_kernels.h"
 
 // Timing experiments only (results are wrong when set): 1 = skip the MFMA/VALU work,
@@ -67,13 +70,16 @@ constexpr int kEpiBytes =
 static_assert(kBM <= kSaLen, "one scale slot per token");
 // vector-memory operations per wave and K block, and the wait that proves block kb landed:
 // operations issued after its copies = weights(kb) + all of blocks kb+1's issue
-constexpr int kVmemPerStep = kBP + 1 + 4;  // token pieces, scales, weight loads
-constexpr int kVmemAfter = kVmemPerStep;  // 10: only block kb+1's operations may still be in flight
-static_assert(kVmemAfter == 10, "the s_waitcnt immediate below assumes 10");
+// Vector-memory operations per wave that fetch one K block: 5 token pieces, 4 weight loads and,
+// for every third block, one copy of the activation scales of three blocks (a token's scales
+// of consecutive K blocks are adjacent in memory while 64 tokens' scales of one block lie in 64
+// different cache lines, and the memory pipeline's cost is per line touched).
+constexpr int kVmemPerStep = kBP + 1 + 4;  // operation slots per block: pieces, (scales), weights
+constexpr int kVmemNoScale = kVmemPerStep - 1;
+static_assert(kVmemPerStep == 10, "the s_waitcnt immediates below assume 10 and 9");
 // s_waitcnt immediate (gfx9 layout): vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14
-constexpr int kVmcntStep = kVmemAfter;
-constexpr int kWaitVmStep = (kVmcntStep & 15) | (7 << 4) | (15 << 8) | ((kVmcntStep >> 4) << 14);
-constexpr int kWaitVm0 = 0 | (7 << 4) | (15 << 8);
+constexpr int wait_vm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+constexpr int kWaitVm0 = wait_vm(0);
 
 typedef const __attribute__((address_space(1))) v4i* gv4i;
 typedef const __attribute__((address_space(1))) float* gf32;
@@ -94,9 +100,10 @@ __device__ __forceinline__ void dma16(const uint8_t* src_lane, uint8_t* dst_wave
   const uint32_t d = __builtin_amdgcn_readfirstlane(lds_offset(dst_wave_uniform));
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(d), "v"(src_lane) : "memory");
 }
-__device__ __forceinline__ void dma4(const float* src_lane, float* dst_wave_uniform) {
+// 12 bytes per lane; lane l's bytes land at dst + l*16 (measured: the fourth dword of a slot is not written)
+__device__ __forceinline__ void dma12(const float* src_lane, float* dst_wave_uniform) {
   const uint32_t d = __builtin_amdgcn_readfirstlane(lds_offset(dst_wave_uniform));
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(d), "v"(src_lane) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx3 %1, off" ::"s"(d), "v"(src_lane) : "memory");
 }
 
 struct AFrag {  // two 16x128 weight tiles in MFMA operand layout (16 registers)
@@ -114,9 +121,10 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   __shared__ __attribute__((aligned(16))) uint8_t lds_b0[kLdsB];
   __shared__ __attribute__((aligned(16))) uint8_t lds_b1[kLdsB];
   __shared__ __attribute__((aligned(16))) uint8_t lds_b2[kLdsB];
-  __shared__ __attribute__((aligned(16))) float lds_sa0[kSaLen];
-  __shared__ __attribute__((aligned(16))) float lds_sa1[kSaLen];
-  __shared__ __attribute__((aligned(16))) float lds_sa2[kSaLen];
+  // activation scales of three consecutive K blocks per token slot (16-byte slots, the layout
+  // the 12-byte copy writes), double-buffered by block triple
+  __shared__ __attribute__((aligned(16))) float lds_sg0[kSaLen * 4];
+  __shared__ __attribute__((aligned(16))) float lds_sg1[kSaLen * 4];
   __shared__ int32_t lds_row[kSaLen];
   __shared__ __attribute__((aligned(16))) uint8_t lds_epi[kEpiBytes];  // amax / store staging
 
@@ -202,13 +210,20 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   const uint32_t lane16 = lane * 16;
   // the tile of the running multiply after which operation i of the next fetch is issued
   auto op_slot = [](int i) { return i < kVmemPerStep - 1 ? 2 * i : kTT - 1; };
-  auto issue_op = [&](int op, uint8_t* lb, float* lsa, AFrag& a, int kb) {
+  // One operation of the fetch of the pos-th block of the walk over K (block min(pos, nkb-1):
+  // past the end the ring re-fetches the last block so that the counts the waits rely on stay
+  // the same).  Operation kBP, the scale copy, exists only for pos % 3 == 0 and brings the
+  // scales of blocks pos..pos+2 (with nkb % 3 != 0 the last copy reads one or two floats past
+  // a token's row: the next row's, or the padding the workspace keeps behind the array).
+  auto issue_op = [&](int op, int pos, uint8_t* lb, AFrag& a) {
     if (DWDP_TILE_DBG & 128) return;
+    const int kb = min(pos, nkb - 1);
     if (op < kBP) {
       const int c = min(wave + kTileWaves * op, kBPieces - 1);
       if (!(DWDP_TILE_DBG & 8)) dma16(act + (b_src[op] + (uint32_t)kb * 128), lb + c * (kTileBytes / 2));
     } else if (op == kBP) {
-      if (!(DWDP_TILE_DBG & 8)) dma4(act_s + (sa_src + (uint32_t)kb), lsa + wave * 64);
+      float* lsg = ((pos / 3) & 1) ? lds_sg1 : lds_sg0;
+      if (!(DWDP_TILE_DBG & 8)) dma12(act_s + (sa_src + (uint32_t)kb), lsg + wave * (64 * 4));
     } else if (!(DWDP_TILE_DBG & 4)) {
       const int j = (op - kBP - 1) >> 1, half = (op - kBP - 1) & 1;
       const uint8_t* base = a_src[j] + (size_t)kb * kTileBytes;  // wave-uniform: scalar registers
@@ -220,26 +235,32 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
                      : "v"(lane16), "s"(base));
     }
   };
-  auto issue = [&](uint8_t* lb, float* lsa, AFrag& a, int kb) {
+  // the whole fetch of position pos (prologue); C = pos % 3 decides whether it has a scale copy
+  auto issue = [&](int pos, bool has_scales, uint8_t* lb, AFrag& a) {
 #pragma unroll
-    for (int op = 0; op < kVmemPerStep; op++) issue_op(op, lb, lsa, a, kb);
+    for (int op = 0; op < kVmemPerStep; op++)
+      if (op != kBP || has_scales) issue_op(op, pos, lb, a);
   };
 
-  // Multiply block kb from (lb, lsa, a) and, spread between its token tiles, issue the
-  // fetches of block kbn into (lbn, lsan, an): issued in one burst the ten operations keep
+  // Multiply block kb from (lb, a) and, spread between its token tiles, issue the fetch of
+  // position kb + 2 into (lbn, an): issued in one burst the operations keep
   // the wave at the memory pipeline's door for as long as the transfers take, one every
   // other tile they slip in under the MFMAs.
   // Token tiles are processed in pairs with two operand buffers (no register copies): while
   // the MFMAs of tile t run, the LDS reads of tile t+1 are already in flight.
-  auto compute = [&](const uint8_t* lb, const float* lsa, const AFrag& a, int kb, uint8_t* lbn, float* lsan,
-                     AFrag& an, int kbn) {
+  // C = kb % 3 is a compile-time constant of each unrolled call: it selects this block's scale
+  // inside its triple and tells whether the fetch issued here (position kb + 2) has a scale copy.
+  auto compute = [&](auto c_const, const uint8_t* lb, const AFrag& a, int kb, uint8_t* lbn, AFrag& an) {
+    constexpr int C = decltype(c_const)::value;
+    constexpr bool kNextHasScales = (C + 2) % 3 == 0;
+    const int pos_n = kb + 2;
     const float w0 = *(cf32)(sw[0] + kb);
     const float w1 = *(cf32)(sw[1] + kb);
     const v8i af0 = cat8(a.t[0][0], a.t[0][1]);
     const v8i af1 = cat8(a.t[1][0], a.t[1][1]);
     const uint8_t* pb0 = lb + b_rd0;
     const uint8_t* pb1 = lb + (b_rd0 ^ 16);  // chunk 2lq+1 sits in the neighbouring slot
-    const float* ps = lsa + lr;
+    const float* ps = (((kb / 3) & 1) ? lds_sg1 : lds_sg0) + lr * 4 + C;
     const v4f zero = {0.f, 0.f, 0.f, 0.f};
     v8i bfx, bfy;
     bfx = cat8(*(const v4i*)pb0, *(const v4i*)pb1);
@@ -265,7 +286,7 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
         if (!(DWDP_TILE_DBG & 32)) {
           if (t + 1 < kTT)  // tile t+1 is always inside the LDS image
             bf_n = cat8(*(const v4i*)(pb0 + (t + 1) * kTileBytes), *(const v4i*)(pb1 + (t + 1) * kTileBytes));
-          sa = ps[t * 16];
+          sa = ps[t * 64];
         }
         if (DWDP_TILE_DBG & 64) {
           acc[0][t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af0, bf, acc[0][t], 0, 0, 0, 0, 0, 0);
@@ -279,7 +300,7 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
       // operation i goes after tile op_slot(i) (always, also past ntt)
 #pragma unroll
       for (int op = 0; op < kVmemPerStep; op++)
-        if (op_slot(op) == t) issue_op(op, lbn, lsan, an, kbn);
+        if (op_slot(op) == t && (op != kBP || kNextHasScales)) issue_op(op, pos_n, lbn, an);
       __builtin_amdgcn_sched_barrier(0);
     };
 #pragma unroll
@@ -293,12 +314,13 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
 
   // "block kb has landed for everyone, and everyone is done with the image that the next
   // issue overwrites": own copies complete (in-order counter), then one barrier.
-  auto publish = [&]() {
+  // n_next: operations of the following block's fetch, the only ones that may be outstanding
+  auto publish = [&](auto n_next) {
     if (DWDP_TILE_DBG & 16) return;
     // pinned between scheduling barriers: nothing of the following issue (its address
     // arithmetic reuses registers of retired loads) may move above the wait
     __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(kWaitVmStep);
+    __builtin_amdgcn_s_waitcnt(wait_vm(decltype(n_next)::value));
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
   };
@@ -307,20 +329,19 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
     asm volatile("" ::"v"(a.t[0][0]), "v"(a.t[0][1]), "v"(a.t[1][0]), "v"(a.t[1][1]));
   };
   AFrag a0 = {}, a1 = {}, a2 = {};
-  // ph(i): the i-th block of the walk over K; past the end the ring re-fetches the last block
-  auto ph = [&](int i) { return min(i, nkb - 1); };
-  issue(lds_b0, lds_sa0, a0, ph(0));
-  issue(lds_b1, lds_sa1, a1, ph(1));
+  using std::integral_constant;
+  issue(0, true, lds_b0, a0);
+  issue(1, false, lds_b1, a1);
   for (int kb = 0; kb < nkb; kb += 3) {
-    publish();
-    compute(lds_b0, lds_sa0, a0, ph(kb), lds_b2, lds_sa2, a2, ph(kb + 2));
+    publish(integral_constant<int, kVmemNoScale>{});  // position kb+1 has no scale copy
+    compute(integral_constant<int, 0>{}, lds_b0, a0, kb, lds_b2, a2);
     if (kb + 1 < nkb) {
-      publish();
-      compute(lds_b1, lds_sa1, a1, ph(kb + 1), lds_b0, lds_sa0, a0, ph(kb + 3));
+      publish(integral_constant<int, kVmemNoScale>{});
+      compute(integral_constant<int, 1>{}, lds_b1, a1, kb + 1, lds_b0, a0);
     }
     if (kb + 2 < nkb) {
-      publish();
-      compute(lds_b2, lds_sa2, a2, ph(kb + 2), lds_b1, lds_sa1, a1, ph(kb + 4));
+      publish(integral_constant<int, kVmemPerStep>{});  // position kb+3 starts a triple
+      compute(integral_constant<int, 2>{}, lds_b2, a2, kb + 2, lds_b1, a1);
     }
   }
   // Drain the ring's surplus copies before LDS is reused.  The fragments are named as
