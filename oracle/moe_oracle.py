@@ -1,8 +1,8 @@
 """CPU oracle for the DWDP MoE-layer hot path.  TEST INFRASTRUCTURE ONLY.
 
 A plain, slow, obviously-correct numpy implementation of what one rank's MoE
-layer computes: router top-k, permutation by expert, block-scaled FP8 (or bf16)
-expert MLP with SwiGLU, weighted combine.  Floating point is fp64 unless a step
+layer computes: router top-k, permutation by expert, block-scaled FP8 (or MXFP4, or
+bf16) expert MLP with SwiGLU, weighted combine.  Floating point is fp64 unless a step
 fixes a precision (stated at the step).  Only tests, the smoke check and the
 benchmark's cpu_baseline leg may import this package; it shares no code with the
 HIP path and never imports it.
@@ -34,6 +34,7 @@ SCORE_SOFTMAX = 0
 SCORE_SIGMOID = 1
 W_BF16 = 0
 W_FP8 = 1
+W_MXFP4 = 2
 
 
 @dataclass(frozen=True)
@@ -124,6 +125,44 @@ def dequant_blocks(codes: np.ndarray, scales: np.ndarray, block: int = 128) -> n
     w = E4M3_TABLE[codes]
     s = np.repeat(np.repeat(scales.astype(np.float64), block, axis=0), block, axis=1)
     return w * s[:R, :C]
+
+
+# --------------------------------------------------------------------------------------
+# MXFP4 weights (OCP Microscaling Formats v1.0): elements are FP4 E2M1 (1 sign, 2 exponent
+# bits with bias 1, 1 mantissa bit: magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6), blocks of 32
+# consecutive elements along K share one E8M0 scale 2^(byte - 127) (0xFF = NaN).  This is
+# the AMD-native analogue of the NVFP4 weights the paper's model uses (its Section 5.1); the
+# paper itself fixes no FP4 arithmetic, so the format definition is the specification.
+# Storage: two codes per byte, element 2i in the low nibble of byte i.
+# --------------------------------------------------------------------------------------
+
+def e2m1_decode(code: int) -> float:
+    """Value of one 4-bit E2M1 code."""
+    sign = -1.0 if (code & 0x8) else 1.0
+    exp = (code >> 1) & 0x3
+    man = code & 0x1
+    if exp == 0:
+        return sign * 0.5 * man                     # subnormal: 0 or 0.5
+    return sign * (1.0 + 0.5 * man) * 2.0 ** (exp - 1)
+
+
+E2M1_TABLE = np.array([e2m1_decode(c) for c in range(16)], dtype=np.float64)
+
+
+def e8m0_decode(code: np.ndarray) -> np.ndarray:
+    """2^(code - 127) for uint8 codes; 255 is NaN."""
+    c = np.asarray(code).astype(np.int64)
+    return np.where(c == 255, np.nan, np.ldexp(1.0, c - 127))
+
+
+def dequant_mxfp4(packed: np.ndarray, scales: np.ndarray, block: int = 32) -> np.ndarray:
+    """fp64 matrix [R,C] from packed E2M1 codes uint8 [R,C/2] and E8M0 scales uint8 [R,C/block]."""
+    R, half = packed.shape
+    C = 2 * half
+    codes = np.empty((R, C), dtype=np.uint8)
+    codes[:, 0::2] = packed & 0xF
+    codes[:, 1::2] = packed >> 4
+    return E2M1_TABLE[codes] * np.repeat(e8m0_decode(scales), block, axis=1)[:, :C]
 
 
 # --------------------------------------------------------------------------------------
@@ -230,7 +269,9 @@ def permute(topk_ids: np.ndarray, spec: LayerSpec):
 @dataclass
 class ExpertNumpy:
     """One expert's weights, logical layouts: w13 [2I,H] (gate rows then up rows), w2 [H,I].
-    FP8: uint8 codes + fp32 scales per 128x128 block.  bf16: float arrays holding bf16 values."""
+    FP8: uint8 codes + fp32 scales per 128x128 block.  MXFP4: packed E2M1 codes (two per byte
+    along the second axis) + uint8 E8M0 scales per 32 elements.  bf16: float arrays holding
+    bf16 values."""
     w13: np.ndarray
     w2: np.ndarray
     s13: Optional[np.ndarray] = None
@@ -239,6 +280,8 @@ class ExpertNumpy:
     def dense(self) -> Tuple[np.ndarray, np.ndarray]:
         if self.s13 is None:
             return self.w13.astype(np.float64), self.w2.astype(np.float64)
+        if self.s13.dtype == np.uint8:
+            return dequant_mxfp4(self.w13, self.s13), dequant_mxfp4(self.w2, self.s2)
         return dequant_blocks(self.w13, self.s13), dequant_blocks(self.w2, self.s2)
 
 
@@ -249,18 +292,20 @@ def silu(g: np.ndarray) -> np.ndarray:
 def expert_mlp(x_rows: np.ndarray, expert: ExpertNumpy, spec: LayerSpec) -> np.ndarray:
     """o = W_down ( QDQ( silu(W_gate x~) * (W_up x~) ) ),  x~ = QDQ(x), rows of x_rows at once.
 
-    QDQ is the per-token, per-128 e4m3 activation quantisation and exists only for FP8
-    weights (FP8 matrix cores need an FP8 activation operand, so the quantisation is part of
-    the function both sides compute); for bf16 weights it is the identity.  fp64 everywhere else.
+    QDQ is the per-token, per-128 e4m3 activation quantisation and exists for FP8 and MXFP4
+    weights (the matrix cores need an FP8 activation operand beside them, so the quantisation
+    is part of the function both sides compute); for bf16 weights it is the identity.  fp64
+    everywhere else.
     """
     I = spec.I
     w13, w2 = expert.dense()
     xr = np.asarray(x_rows, dtype=np.float64)
-    if spec.w_dtype == W_FP8:
+    quantised = spec.w_dtype in (W_FP8, W_MXFP4)
+    if quantised:
         xr = qdq_act(xr)[0]
     gu = xr @ w13.T
     h = silu(gu[:, :I]) * gu[:, I:]
-    if spec.w_dtype == W_FP8:
+    if quantised:
         h = qdq_act(h)[0]
     return h @ w2.T
 

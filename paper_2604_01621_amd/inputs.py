@@ -31,6 +31,8 @@ SCORE_SOFTMAX = 0
 SCORE_SIGMOID = 1
 W_BF16 = 0
 W_FP8 = 1
+W_MXFP4 = 2        # FP4 E2M1 codes, one E8M0 scale per 32 elements along K (OCP MX)
+MX_BLOCK = 32
 BLOCK = 128          # side of a weight scale block; also the activation quantisation group
 E4M3_MAX = 448.0
 
@@ -164,6 +166,30 @@ def _quant_block_fp8(w: torch.Tensor):
     return codes, scale.to(torch.float32)
 
 
+def _quant_mxfp4(w: torch.Tensor):
+    """fp32 [R,C] -> (packed E2M1 codes uint8 [R,C/2], E8M0 scales uint8 [R,C/32]).
+
+    Input synthesis only (how random weights become MXFP4 test data; the layer's arithmetic
+    starts from the codes): shared exponent = floor(log2(block amax)) - 2 (2 = exponent of
+    the largest E2M1 value, 6 = 1.5 * 2^2), elements rounded to the nearest E2M1 value, ties
+    to the even code, saturating at +-6.
+    """
+    R, C = w.shape
+    wb = w.view(R, C // MX_BLOCK, MX_BLOCK)
+    amax = wb.abs().amax(dim=2)
+    e = torch.where(amax > 0, torch.floor(torch.log2(amax)) - 2, torch.zeros_like(amax)).clamp_(-127, 127)
+    q = (wb / torch.exp2(e)[:, :, None]).abs()
+    # thresholds between neighbouring magnitudes 0, .5, 1, 1.5, 2, 3, 4, 6; `up` = the tie goes to the upper
+    # neighbour (its code is the even one)
+    code = torch.zeros_like(q, dtype=torch.uint8)
+    for thr, up in ((0.25, False), (0.75, True), (1.25, False), (1.75, True), (2.5, False), (3.5, True), (5.0, False)):
+        code += ((q > thr) | ((q == thr) & up)).to(torch.uint8)
+    code |= (wb < 0).to(torch.uint8) << 3
+    code = code.view(R, C)
+    packed = (code[:, 0::2] | (code[:, 1::2] << 4)).contiguous()
+    return packed, (e + 127).to(torch.uint8)
+
+
 def make_expert_weights(cfg: MoEConfig, seed: int, device="cpu", n: Optional[int] = None,
                         std: float = 0.02) -> ExpertWeights:
     """W ~ N(0, std) per expert slot; FP8 workloads quantise per 128x128 block so that the
@@ -179,6 +205,15 @@ def make_expert_weights(cfg: MoEConfig, seed: int, device="cpu", n: Optional[int
             w2[e] = (torch.randn(H, I, generator=g, device=device) * std).to(torch.bfloat16)
         return ExpertWeights(w13, w2, None, None)
     assert H % BLOCK == 0 and I % BLOCK == 0
+    if cfg.w_dtype == W_MXFP4:
+        w13 = torch.empty(n, 2 * I, H // 2, dtype=torch.uint8, device=device)
+        w2 = torch.empty(n, H, I // 2, dtype=torch.uint8, device=device)
+        s13 = torch.empty(n, 2 * I, H // MX_BLOCK, dtype=torch.uint8, device=device)
+        s2 = torch.empty(n, H, I // MX_BLOCK, dtype=torch.uint8, device=device)
+        for e in range(n):
+            w13[e], s13[e] = _quant_mxfp4(torch.randn(2 * I, H, generator=g, device=device) * std)
+            w2[e], s2[e] = _quant_mxfp4(torch.randn(H, I, generator=g, device=device) * std)
+        return ExpertWeights(w13, w2, s13, s2)
     w13 = torch.empty(n, 2 * I, H, dtype=torch.uint8, device=device)
     w2 = torch.empty(n, H, I, dtype=torch.uint8, device=device)
     s13 = torch.empty(n, 2 * I // BLOCK, H // BLOCK, dtype=torch.float32, device=device)
@@ -194,6 +229,8 @@ def expert_bytes(cfg: MoEConfig) -> int:
     H, I = cfg.H, cfg.I
     if cfg.w_dtype == W_BF16:
         return 2 * (2 * I * H + H * I)
+    if cfg.w_dtype == W_MXFP4:
+        return 3 * I * H // 2 + 3 * I * H // MX_BLOCK
     return 3 * I * H + 4 * ((2 * I // BLOCK) * (H // BLOCK) + (H // BLOCK) * (I // BLOCK))
 
 
