@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--copy-engine", type=int, default=1, help="pipeline workload: 0 hipMemcpyAsync per slice, "
                                                                "1 copy-plan kernel")
     ap.add_argument("--copy-wgs", type=int, default=512, help="pipeline workload: workgroups of the copy-plan kernel")
+    ap.add_argument("--weights", default="fp8", choices=["fp8", "mxfp4"],
+                    help="expert weight format of the decode/prefill/skew workloads: block-scaled FP8 (the "
+                         "headline configuration) or MXFP4 (FP4 codes with a power-of-two scale per 32)")
     ap.add_argument("--merge-baseline", action="store_true",
                     help="pipeline workload: merge resident and staged experts into one contiguous image before "
                          "every layer (the naive split-weight baseline) instead of reading them in place")
@@ -100,6 +103,9 @@ def main():
         return
 
     cfg, x, logits, bias = inputs.make_layer_inputs(args.workload, args.seed, device=dev, T=args.T)
+    if args.weights == "mxfp4" and cfg.w_dtype == inputs.W_FP8:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, w_dtype=inputs.W_MXFP4)
     w = inputs.make_expert_weights(cfg, args.seed, device=dev)
     stream = torch.cuda.Stream()
     ctx = binding.Context(cfg, stream=stream)
@@ -140,9 +146,14 @@ def main():
     ms_per_step = dt / args.steps * 1e3
 
     fp8 = cfg.w_dtype == inputs.W_FP8
+    mx = cfg.w_dtype == inputs.W_MXFP4
     el = 1 if fp8 else 2
-    b13 = 2 * cfg.I * cfg.H * el + (4 * (2 * cfg.I // 128) * (cfg.H // 128) if fp8 else 0)
-    b2 = cfg.H * cfg.I * el + (4 * (cfg.H // 128) * (cfg.I // 128) if fp8 else 0)
+    if mx:      # packed codes + packed scales as the kernels read them
+        b13 = 2 * cfg.I * cfg.H // 2 + binding.mx_scale_bytes(2 * cfg.I, cfg.H)
+        b2 = cfg.H * cfg.I // 2 + binding.mx_scale_bytes(cfg.H, cfg.I)
+    else:
+        b13 = 2 * cfg.I * cfg.H * el + (4 * (2 * cfg.I // 128) * (cfg.H // 128) if fp8 else 0)
+        b2 = cfg.H * cfg.I * el + (4 * (cfg.H // 128) * (cfg.I // 128) if fp8 else 0)
     # which kernel family serves which expert (the library's default threshold: 16 rows)
     smr = args.stream_max_rows if args.stream_max_rows is not None else 16
     if not fp8 or cfg.T <= smr:
@@ -174,18 +185,19 @@ def main():
 
     roof = roofline("gemm1", "gemm1_tile", b13, 2 * 2 * cfg.I * cfg.H, "GEMM-1 (gate/up + SwiGLU)")
     roof2 = roofline("gemm2", "gemm2_tile", b2, 2 * cfg.I * cfg.H, "GEMM-2 (down)")
-    if args.stream_max_rows is None:
+    if args.stream_max_rows is None and not mx:
         roof["traffic"] = PROFILED_TRAFFIC.get((args.workload, args.seed, cfg.T))
 
     out = {
         "metric": "moe_layer_tokens_per_s", "value": cfg.T / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "fp8_e4m3" if fp8 else "bf16", "data": "synthetic",
+        "dtype": "fp8_e4m3" if fp8 else ("mxfp4 weights x fp8_e4m3 activations" if mx else "bf16"), "data": "synthetic",
         "config": {"workload": f"{args.workload}: DeepSeek-R1-shaped MoE layer" if args.workload != "tiny"
                    else "tiny bf16 MoE layer", "T": cfg.T, "H": cfg.H, "I": cfg.I, "E": cfg.E, "K": cfg.K,
                    "shared_experts": cfg.has_shared, "active_expert_slots": active, "token_expert_pairs": pairs,
-                   "weights": "FP8 e4m3 + fp32 128x128 block scales, all resident" if fp8 else "bf16, all resident"},
+                   "weights": "FP8 e4m3 + fp32 128x128 block scales, all resident" if fp8 else
+                   ("MXFP4 (E2M1 + E8M0 per 32), all resident" if mx else "bf16, all resident")},
         "roofline": roof, "roofline_gemm2": roof2, "stage_ms": stage_ms,
         "experts_streamed": n_stream, "experts_tiled": n_tile,
         "layer_weight_gbs": active * (b13 + b2) / (ms_per_step * 1e-3) / 1e9,

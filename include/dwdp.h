@@ -44,7 +44,7 @@ typedef enum {
 } dwdp_status;
 
 enum { DWDP_SCORE_SOFTMAX = 0, DWDP_SCORE_SIGMOID = 1 };
-enum { DWDP_W_BF16 = 0, DWDP_W_FP8 = 1 };
+enum { DWDP_W_BF16 = 0, DWDP_W_FP8 = 1, DWDP_W_MXFP4 = 2 };
 
 /* Shape and routing parameters of one MoE layer; all layers of a context share them. */
 typedef struct {
@@ -72,6 +72,11 @@ typedef struct {
  *         kernels stream whole 2 KiB tiles); s13 fp32 [2I/128, H/128], s2 fp32
  *         [H/128, I/128] row-major: one scale per 128x128 block of the logical matrix,
  *         weight = decode(byte) * scale.  Pointers 16-byte aligned.
+ *   MXFP4: FP4 E2M1 codes, two per byte, with one E8M0 scale (2^(byte-127)) per 32 elements
+ *         along K (OCP Microscaling Formats v1.0; the analogue on this hardware of the NVFP4
+ *         weights of the paper's model, Section 5.1).  Codes and scales in the layouts written
+ *         by dwdp_pack_mxfp4_weight; s13 / s2 point at the packed scale bytes (the pointer
+ *         type is only nominal).  Pointers 16-byte aligned.
  *   bf16: 2 bytes/element, plain row-major; s13 = s2 = NULL.
  */
 typedef struct {
@@ -150,7 +155,8 @@ dwdp_status dwdp_prefetch_layer(dwdp_ctx* ctx, int32_t layer, const void* const*
                                 const size_t* bytes, int32_t n_peers, int32_t n_params, size_t slice_bytes);
 
 /*
- * Kernel selection of the FP8 grouped GEMM.  Experts with 1..max_rows sorted rows are
+ * Kernel selection of the FP8 grouped GEMM (MXFP4 weights always use their weight-streaming
+ * kernels).  Experts with 1..max_rows sorted rows are
  * computed by the weight-streaming kernels (weights straight to registers, 16 token rows per
  * pass over the weights), experts with more rows by the LDS-tiled kernels (288-token tiles,
  * weights read once per tile).  Default 16.  0 sends every
@@ -172,6 +178,21 @@ dwdp_status dwdp_set_stream_max_rows(dwdp_ctx* ctx, int32_t max_rows);
  * compute stream.
  */
 dwdp_status dwdp_pack_fp8_weight(dwdp_ctx* ctx, const void* src, void* dst, int64_t rows, int64_t cols);
+
+/*
+ * The same preparation for MXFP4 weights: src_codes [rows, cols/2] (element 2i in the low
+ * nibble of byte i) and src_scales uint8 [rows, cols/32], both row-major, are rearranged into
+ *   dst_codes  [rows * cols / 2] bytes: 16-row x 128-column tiles of 1 KiB, row-of-tiles first;
+ *              inside a tile byte (q*16 + r)*16 + b holds packed byte q*16 + b of row r's 64
+ *              bytes of that K block -- lane q*16+r of a wavefront feeds elements
+ *              32q..32q+31 of row r to a 16x16x128 matrix-core operand;
+ *   dst_scales [rows/16 * ceil(cols/512) * 256] bytes: per row-of-tiles and group of four K
+ *              blocks, lane q*16+r's dword holds the scales of (row r, K blocks 4g..4g+3,
+ *              32-element sub-block q), padded with 127.
+ * rows % 16 == 0, cols % 128 == 0 (DWDP_ESHAPE otherwise).  Enqueued on the compute stream.
+ */
+dwdp_status dwdp_pack_mxfp4_weight(dwdp_ctx* ctx, const void* src_codes, const void* src_scales, void* dst_codes,
+                                   void* dst_scales, int64_t rows, int64_t cols);
 
 /*
  * How dwdp_prefetch_layer moves the bytes of its copy plan.
@@ -207,7 +228,8 @@ dwdp_status dwdp_build_copy_plan(const void* const* src, void* const* dst, const
  * `layer` names the layer the table belongs to: when a dwdp_prefetch_layer of it is pending,
  * the copies wait for the staged experts; the staging buffer still belongs to the layer until
  * its dwdp_moe_forward (called with the merged table) has run.  Experts that already lie
- * back to back in the source are moved with one copy.
+ * back to back in the source are moved with one copy.  bf16 and FP8 weights (DWDP_ESHAPE for
+ * MXFP4).
  */
 dwdp_status dwdp_merge_experts(dwdp_ctx* ctx, int32_t layer, const dwdp_expert_ptrs* table_host, int32_t n_slots,
                                void* w13_out, float* s13_out, void* w2_out, float* s2_out,

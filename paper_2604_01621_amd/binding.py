@@ -62,6 +62,7 @@ def _load() -> C.CDLL:
     lib.dwdp_set_stream_max_rows.argtypes = [vp, i32]
     lib.dwdp_set_copy_engine.argtypes = [vp, i32, i32]
     lib.dwdp_pack_fp8_weight.argtypes = [vp, vp, vp, C.c_int64, C.c_int64]
+    lib.dwdp_pack_mxfp4_weight.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int64]
     lib.dwdp_profile_enable.argtypes = [vp, i32]
     lib.dwdp_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32)]
     lib.dwdp_timeline_enable.argtypes = [vp, i32]
@@ -102,6 +103,11 @@ def build_copy_plan(src: Sequence[int], dst: Sequence[int], nbytes: Sequence[int
     if st != OK:
         raise DwdpError(st, "dwdp_build_copy_plan")
     return [(pd[i] or 0, ps[i] or 0, pb[i]) for i in range(m)]
+
+
+def mx_scale_bytes(rows: int, cols: int) -> int:
+    """Bytes of the packed MXFP4 scales of one [rows, cols] matrix (see dwdp_pack_mxfp4_weight)."""
+    return (rows // 16) * ((cols // 128 + 3) // 4) * 256
 
 
 def expert_table(weights: ExpertWeights, device=None) -> torch.Tensor:
@@ -191,11 +197,37 @@ class Context:
         for i in range(n):
             self._check(lib.dwdp_pack_fp8_weight(self.h, _ptr(s2[i]), _ptr(d2[i]), rows, cols))
 
+    def dwdp_pack_mxfp4_weight(self, codes: torch.Tensor, scales: torch.Tensor, codes_out: torch.Tensor,
+                               scales_out: torch.Tensor):
+        """codes uint8 [n, rows, cols/2], scales uint8 [n, rows, cols/32] -> streaming layouts, matrix by matrix."""
+        n, rows, half = codes.shape
+        cols = 2 * half
+        assert scales.shape == (n, rows, cols // 32) and codes_out.shape == codes.shape
+        assert scales_out.shape == (n, mx_scale_bytes(rows, cols))
+        for i in range(n):
+            self._check(lib.dwdp_pack_mxfp4_weight(self.h, _ptr(codes[i]), _ptr(scales[i]), _ptr(codes_out[i]),
+                                                   _ptr(scales_out[i]), rows, cols))
+
     def pack_experts(self, w: ExpertWeights) -> ExpertWeights:
-        """Device copy of `w` in the layout the kernels read: FP8 codes tile-major, scales and
-        bf16 weights unchanged (shared, not copied)."""
+        """Device copy of `w` in the layout the kernels read: FP8 codes tile-major (scales
+        shared, not copied), MXFP4 codes and scales in their streaming layouts, bf16 weights
+        unchanged."""
         if w.s13 is None:
             return w
+        if w.s13.dtype == torch.uint8:      # MXFP4
+            n, r13, c13 = w.w13.shape[0], w.w13.shape[1], 2 * w.w13.shape[2]
+            r2, c2 = w.w2.shape[1], 2 * w.w2.shape[2]
+            p13, p2 = torch.empty_like(w.w13), torch.empty_like(w.w2)
+            q13 = torch.empty(n, mx_scale_bytes(r13, c13), dtype=torch.uint8, device=w.w13.device)
+            q2 = torch.empty(n, mx_scale_bytes(r2, c2), dtype=torch.uint8, device=w.w13.device)
+            torch.cuda.synchronize()
+            self.dwdp_pack_mxfp4_weight(w.w13, w.s13, p13, q13)
+            self.dwdp_pack_mxfp4_weight(w.w2, w.s2, p2, q2)
+            if self.stream is not None:
+                self.stream.synchronize()
+            else:
+                torch.cuda.synchronize()
+            return ExpertWeights(p13, p2, q13, q2)
         p13, p2 = torch.empty_like(w.w13), torch.empty_like(w.w2)
         torch.cuda.synchronize()      # `w` may still be being written on another stream
         self.dwdp_pack_fp8_weight(w.w13, p13)

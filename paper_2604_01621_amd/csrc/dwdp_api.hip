@@ -87,8 +87,8 @@ static dwdp_status check_config(const dwdp_config* c) {
     return fail(nullptr, DWDP_EINVAL, "non-positive size in cfg");
   if (c->score_fn != DWDP_SCORE_SOFTMAX && c->score_fn != DWDP_SCORE_SIGMOID)
     return fail(nullptr, DWDP_EINVAL, "score_fn must be DWDP_SCORE_SOFTMAX or DWDP_SCORE_SIGMOID");
-  if (c->w_dtype != DWDP_W_BF16 && c->w_dtype != DWDP_W_FP8)
-    return fail(nullptr, DWDP_EINVAL, "w_dtype must be DWDP_W_BF16 or DWDP_W_FP8");
+  if (c->w_dtype != DWDP_W_BF16 && c->w_dtype != DWDP_W_FP8 && c->w_dtype != DWDP_W_MXFP4)
+    return fail(nullptr, DWDP_EINVAL, "w_dtype must be DWDP_W_BF16, DWDP_W_FP8 or DWDP_W_MXFP4");
   if (c->has_shared != 0 && c->has_shared != 1) return fail(nullptr, DWDP_EINVAL, "has_shared must be 0 or 1");
   if (c->H % 128 || c->I % 128) return fail(nullptr, DWDP_ESHAPE, "H and I must be multiples of 128");
   if (c->E > 1024 || c->K > c->E || c->K > 32) return fail(nullptr, DWDP_ESHAPE, "need K <= E <= 1024 and K <= 32");
@@ -124,7 +124,7 @@ extern "C" dwdp_status dwdp_create(const dwdp_config* cfg, void* compute_stream,
   const size_t T = (size_t)(cfg->T_max > 0 ? cfg->T_max : 1);
   const size_t K = cfg->K, H = cfg->H, I = cfg->I, E = cfg->E;
   c->rows_max = T * K + (cfg->has_shared ? T : 0);
-  const bool fp8 = cfg->w_dtype == DWDP_W_FP8;
+  const bool fp8 = cfg->w_dtype != DWDP_W_BF16;  // FP8 activations and intermediates (FP8 and MXFP4 weights)
   size_t bytes[DWDP_N_WS];
   bytes[DWDP_WS_TOPK_IDS] = T * K * 4;
   bytes[DWDP_WS_TOPK_W] = T * K * 4;
@@ -287,12 +287,14 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
   int32_t* inv = (int32_t*)ctx->ws[DWDP_WS_INV_PERM];
 
   GemmArgs ga{table, off, perm, ctx->n_slots, c.E, T, c.H, c.I, c.K};
-  const bool fp8 = c.w_dtype == DWDP_W_FP8;
-  // Experts with 1..smr rows stream their weights; the others go through the LDS-tiled kernel.
+  const bool mx = c.w_dtype == DWDP_W_MXFP4;
+  const bool fp8 = c.w_dtype != DWDP_W_BF16;  // FP8 activations and intermediates (FP8 and MXFP4 weights)
+  // Experts with 1..smr rows stream their weights; the others go through the LDS-tiled kernel
+  // (FP8 weights only: MXFP4 weights always stream).
   const int rows = T * c.K + (c.has_shared ? T : 0);
   const int smr = ctx->stream_max_rows;
-  const bool use_tile = fp8 && T > smr;  // an expert holds at most T rows
-  const bool use_stream = smr > 0;
+  const bool use_tile = fp8 && !mx && T > smr;  // an expert holds at most T rows
+  const bool use_stream = mx || smr > 0;
   TileSched ts{ctx->mt_expert, ctx->mt_row0, ctx->n_mtiles, 0};
   if (use_tile) ts.n_mt_max = tile_mtiles_cap(rows, ctx->n_slots, smr);
   // Two launches prepare the GEMMs: routing with the (independent) activation quantisation
@@ -325,11 +327,19 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
   if (fp8) {
     if (use_stream) {
       if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM1), sc));
-      launch_gemm1_fp8(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
-                       (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], sc);
+      if (mx)
+        launch_gemm1_mx(ga, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
+                        (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], sc);
+      else
+        launch_gemm1_fp8(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
+                         (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], sc);
       if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM2), sc));
-      launch_gemm2_fp8(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
-                       ctx->ws[DWDP_WS_YP], sc);
+      if (mx)
+        launch_gemm2_mx(ga, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
+                        ctx->ws[DWDP_WS_YP], sc);
+      else
+        launch_gemm2_fp8(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
+                         ctx->ws[DWDP_WS_YP], sc);
       if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfStreamEnd), sc));
       if (two) HIP_TRY(ctx, hipEventRecord(ctx->join_ev, ctx->aux));
     } else if (prof) {
@@ -475,6 +485,8 @@ extern "C" dwdp_status dwdp_merge_experts(dwdp_ctx* ctx, int32_t layer, const dw
     return fail(ctx, DWDP_EINVAL, "dwdp_merge_experts: NULL pointer");
   const dwdp_config& c = ctx->cfg;
   if (layer < 0 || layer >= c.n_layers) return fail(ctx, DWDP_EINVAL, "layer %d outside [0,%d)", layer, c.n_layers);
+  if (c.w_dtype == DWDP_W_MXFP4)
+    return fail(ctx, DWDP_ESHAPE, "dwdp_merge_experts: the merge baseline is built for bf16 and FP8 weights");
   const bool fp8 = c.w_dtype == DWDP_W_FP8;
   if (fp8 && (!s13_out || !s2_out)) return fail(ctx, DWDP_EINVAL, "dwdp_merge_experts: scale outputs are NULL");
   // a pending prefetch of this layer: the merge reads the staged experts, so it waits for them
@@ -542,6 +554,20 @@ extern "C" dwdp_status dwdp_pack_fp8_weight(dwdp_ctx* ctx, const void* src, void
   if (rows * cols == 0) return DWDP_OK;
   if (!src || !dst || src == dst) return fail(ctx, DWDP_EINVAL, "dwdp_pack_fp8_weight: NULL or aliased pointers");
   launch_pack_fp8_tiles(src, dst, rows, (int)cols, ctx->compute);
+  HIP_TRY(ctx, hipGetLastError());
+  return DWDP_OK;
+}
+
+extern "C" dwdp_status dwdp_pack_mxfp4_weight(dwdp_ctx* ctx, const void* src_codes, const void* src_scales,
+                                              void* dst_codes, void* dst_scales, int64_t rows, int64_t cols) {
+  if (!ctx) return DWDP_EINVAL;
+  if (rows < 0 || cols < 0) return fail(ctx, DWDP_EINVAL, "dwdp_pack_mxfp4_weight: negative size");
+  if (rows % 16 || cols % 128 || cols > (1 << 30))
+    return fail(ctx, DWDP_ESHAPE, "dwdp_pack_mxfp4_weight: rows must be a multiple of 16 and cols of 128");
+  if (rows * cols == 0) return DWDP_OK;
+  if (!src_codes || !src_scales || !dst_codes || !dst_scales || src_codes == dst_codes || src_scales == dst_scales)
+    return fail(ctx, DWDP_EINVAL, "dwdp_pack_mxfp4_weight: NULL or aliased pointers");
+  launch_pack_mxfp4(src_codes, src_scales, dst_codes, dst_scales, rows, (int)cols, ctx->compute);
   HIP_TRY(ctx, hipGetLastError());
   return DWDP_OK;
 }

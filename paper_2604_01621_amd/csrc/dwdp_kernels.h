@@ -87,6 +87,13 @@ void launch_gemm2_fp8(const GemmArgs& a, int max_rows, const uint8_t* hq, const 
                       hipStream_t stream);
 void launch_gemm2_fp8_tile(const GemmArgs& a, const TileSched& ts, const uint8_t* hq, const float* hs, void* yp,
                            hipStream_t stream);
+// MXFP4 weights (layouts of launch_pack_mxfp4), FP8 activations: same results as the FP8 pair above
+void launch_gemm1_mx(const GemmArgs& a, const uint8_t* xq, const float* xs, uint8_t* hq, float* hs,
+                     hipStream_t stream);
+void launch_gemm2_mx(const GemmArgs& a, const uint8_t* hq, const float* hs, void* yp, hipStream_t stream);
+// Row-major packed E2M1 codes [rows, cols/2] and E8M0 scales [rows, cols/32] -> the streaming layouts.
+void launch_pack_mxfp4(const void* codes, const void* scales, void* codes_out, void* scales_out, long rows, int cols,
+                       hipStream_t stream);
 // bf16 weights and activations: h fp32 [rows,I]; yp fp32 [rows,H]
 void launch_gemm1_bf16(const GemmArgs& a, const void* x, void* h, hipStream_t stream);
 void launch_gemm2_bf16(const GemmArgs& a, const void* h, void* yp, hipStream_t stream);

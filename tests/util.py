@@ -29,8 +29,9 @@ def to_np(t):
 
 
 def tolerance(cfg) -> float:
-    """Parity bar: max |y - ref| / max |ref| <= 2e-2 with FP8 weights, 5e-3 with bf16 weights."""
-    return 2e-2 if cfg.w_dtype == inputs.W_FP8 else 5e-3
+    """Parity bar: max |y - ref| / max |ref| <= 2e-2 with FP8 activations (FP8 or MXFP4 weights:
+    both sides decode the same weight codes exactly), 5e-3 with bf16 weights."""
+    return 5e-3 if cfg.w_dtype == inputs.W_BF16 else 2e-2
 
 
 def gpu_forward(ctx, cfg, x, logits, bias, table, layer=0):
