@@ -31,7 +31,16 @@
 // t is folded into the accumulators after the MFMAs of tile t+1 have been issued, so the
 // VALU never waits for the matrix pipe.
 //
-// Token tiles of 16 beyond the expert's row count are skipped in the multiply.
+// The multiply of a K block is a chain of token-tile pairs, each behind one scalar branch
+// (pairs beyond the expert's row count are skipped; with an odd tile count the last pair
+// multiplies one tile of repeated rows), and inside a pair the code is straight-line: the
+// LDS read of tile t+1's operand, the two MFMAs of tile t each followed by the five VALU
+// operations that scale tile t-1's products, the LDS read of tile t+1's activation scale.
+// LDS reads return in order, so every use waits for exactly its own read (lgkmcnt(n) with
+// the younger reads still in flight).  That only works while no scalar load is pending
+// (scalar loads share the counter and return out of order: with one in flight every wait
+// becomes a wait for everything), so the weight scales of block kb+1 are loaded at the end
+// of block kb's multiply and waited for together with the vector-memory wait.
 // Workgroups are numbered so that all weight panels of one M tile run on the same XCD back
 // to back and share the token rows in its L2: block b runs on XCD b % 8 and handles M tile
 // (b/8 / n_panels) * 8 + b % 8, panel (b/8) % n_panels.
@@ -41,13 +50,15 @@
 // quantisation of h.  GEMM-2: wave w owns rows 32w..32w+31 of the 256-row panel, bf16 store
 // through an LDS transpose.  Experts with few rows are left to the streaming kernels.
 #include <type_traits>
+#include <utility>
 
 #include "dwdp_kernels.h"
 
 // Timing experiments only (results are wrong when set): 1 = skip the MFMA/VALU work,
 // 16 = no per-block wait and barrier, 32 = no LDS operand reads, 64 = no VALU scaling,
 // 128 = no global loads or copies at all, 4 = no weight loads, 8 = no token copies,
-// 512 = every workgroup reads the same (L2-resident) weight panel.
+// 512 = every workgroup reads the same (L2-resident) weight panel, 1024 = print the shader
+// clock of two workgroups (cycle counter over the 100 MHz counter), 2048 = no scale products.
 // Never set in a product build.
 #ifndef DWDP_TILE_DBG
 #define DWDP_TILE_DBG 0
@@ -58,6 +69,10 @@ namespace dwdp {
 constexpr int kBM = kTileM;     // tokens per workgroup tile (288)
 constexpr int kTT = kBM / 16;   // token tiles per workgroup (18)
 constexpr int kTileWaves = 8;
+#ifndef DWDP_TILE_BDEPTH
+#define DWDP_TILE_BDEPTH 1
+#endif
+constexpr int kBDepth = DWDP_TILE_BDEPTH;  // token tiles whose LDS operand reads run ahead of the multiply
 constexpr int kTileThreads = 64 * kTileWaves;
 constexpr int kLdsB = kTT * kTileBytes;  // one token image: 36 KiB
 constexpr int kBPieces = 2 * kTT;        // 1 KiB pieces of a token image
@@ -79,6 +94,8 @@ constexpr int kVmemNoScale = kVmemPerStep - 1;
 static_assert(kVmemPerStep == 10, "the s_waitcnt immediates below assume 10 and 9");
 // s_waitcnt immediate (gfx9 layout): vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14
 constexpr int wait_vm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+// the same with lgkmcnt(0): scalar loads and LDS operations have completed as well
+constexpr int wait_vm_lgkm0(int n) { return (n & 15) | (7 << 4) | (0 << 8) | ((n >> 4) << 14); }
 constexpr int kWaitVm0 = wait_vm(0);
 
 typedef const __attribute__((address_space(1))) v4i* gv4i;
@@ -106,6 +123,16 @@ __device__ __forceinline__ void dma12(const float* src_lane, float* dst_wave_uni
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx3 %1, off" ::"s"(d), "v"(src_lane) : "memory");
 }
 
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), in order
+template <int... Is, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F&& f) {
+  (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
 struct AFrag {  // two 16x128 weight tiles in MFMA operand layout (16 registers)
   v4i t[2][2];
 };
@@ -128,6 +155,8 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   __shared__ int32_t lds_row[kSaLen];
   __shared__ __attribute__((aligned(16))) uint8_t lds_epi[kEpiBytes];  // amax / store staging
 
+  long long dbg_c0 = 0, dbg_w0 = 0;
+  if (DWDP_TILE_DBG & 1024) { dbg_c0 = clock64(); dbg_w0 = wall_clock64(); }
   const int xcd = blockIdx.x & 7;
   const int s = blockIdx.x >> 3;
   const int mq = s / n_panels;
@@ -209,13 +238,13 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   // fragment keeps its registers, and nothing reads them between issue and wait.
   const uint32_t lane16 = lane * 16;
   // the tile of the running multiply after which operation i of the next fetch is issued
-  auto op_slot = [](int i) { return i < kVmemPerStep - 1 ? 2 * i : kTT - 1; };
+  auto op_slot = [](int i) { return i < kVmemPerStep - 1 ? 2 * i + 1 : kTT - 1; };
   // One operation of the fetch of the pos-th block of the walk over K (block min(pos, nkb-1):
   // past the end the ring re-fetches the last block so that the counts the waits rely on stay
   // the same).  Operation kBP, the scale copy, exists only for pos % 3 == 0 and brings the
   // scales of blocks pos..pos+2 (with nkb % 3 != 0 the last copy reads one or two floats past
   // a token's row: the next row's, or the padding the workspace keeps behind the array).
-  auto issue_op = [&](int op, int pos, uint8_t* lb, AFrag& a) {
+  auto issue_op = [&](int op, int pos, uint8_t* lb, AFrag& a) __attribute__((always_inline)) {
     if (DWDP_TILE_DBG & 128) return;
     const int kb = min(pos, nkb - 1);
     if (op < kBP) {
@@ -242,6 +271,11 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
       if (op != kBP || has_scales) issue_op(op, pos, lb, a);
   };
 
+  // Weight scales of the block about to be multiplied: scalar loads issued at the end of the
+  // previous block's multiply and waited for in publish(), so that no scalar load is pending
+  // while LDS reads are in flight (both count on lgkmcnt, and with a scalar load outstanding
+  // every wait on an LDS read has to be a wait for everything).
+  float wc0 = *(cf32)(sw[0]), wc1 = *(cf32)(sw[1]);
   // Multiply block kb from (lb, a) and, spread between its token tiles, issue the fetch of
   // position kb + 2 into (lbn, an): issued in one burst the operations keep
   // the wave at the memory pipeline's door for as long as the transfers take, one every
@@ -250,65 +284,112 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   // the MFMAs of tile t run, the LDS reads of tile t+1 are already in flight.
   // C = kb % 3 is a compile-time constant of each unrolled call: it selects this block's scale
   // inside its triple and tells whether the fetch issued here (position kb + 2) has a scale copy.
-  auto compute = [&](auto c_const, const uint8_t* lb, const AFrag& a, int kb, uint8_t* lbn, AFrag& an) {
+  auto compute = [&](auto c_const, const uint8_t* lb, const AFrag& a, int kb, uint8_t* lbn, AFrag& an) __attribute__((always_inline)) {
     constexpr int C = decltype(c_const)::value;
     constexpr bool kNextHasScales = (C + 2) % 3 == 0;
     const int pos_n = kb + 2;
-    const float w0 = *(cf32)(sw[0] + kb);
-    const float w1 = *(cf32)(sw[1] + kb);
+    const float w0 = wc0, w1 = wc1;
     const v8i af0 = cat8(a.t[0][0], a.t[0][1]);
     const v8i af1 = cat8(a.t[1][0], a.t[1][1]);
     const uint8_t* pb0 = lb + b_rd0;
     const uint8_t* pb1 = lb + (b_rd0 ^ 16);  // chunk 2lq+1 sits in the neighbouring slot
     const float* ps = (((kb / 3) & 1) ? lds_sg1 : lds_sg0) + lr * 4 + C;
     const v4f zero = {0.f, 0.f, 0.f, 0.f};
-    v8i bfx, bfy;
-    bfx = cat8(*(const v4i*)pb0, *(const v4i*)pb1);
-    bfy = bfx;
     // The scaling of tile t-1's products is issued after the MFMAs of tile t, so the VALU
-    // never waits for an MFMA result: two product sets (px, py) and two activation scales
-    // alternate like the operands.  Tile t's scale is only needed by that later scaling, so
-    // it is read from LDS together with tile t+1's operand.
-    v4f px0 = zero, px1 = zero, py0 = zero, py1 = zero;
-    float sax = 0.f, say = 0.f;
-    auto fold = [&](int t, const v4f& p0, const v4f& p1, float sa) {
-      if (t >= 0 && t < ntt && !(DWDP_TILE_DBG & (1 | 64))) {
-        const float s0 = sa * w0, s1 = sa * w1;
-#pragma unroll
-        for (int i = 0; i < 4; i++) acc[0][t][i] = fmaf(p0[i], s0, acc[0][t][i]);
-#pragma unroll
-        for (int i = 0; i < 4; i++) acc[1][t][i] = fmaf(p1[i], s1, acc[1][t][i]);
+    // never waits for an MFMA result: two operand buffers (bfx, bfy), two product sets
+    // (px, py) and two activation scales alternate.  Tile t's scale is only needed by that
+    // later scaling, so it is read from LDS together with tile t+1's operand.
+    v8i bf[kBDepth + 1];
+    v4f p0[2] = {zero, zero}, p1[2] = {zero, zero};
+    float sa[2] = {0.f, 0.f};
+    auto read_b = [&](int t) __attribute__((always_inline)) -> v8i {
+      if (DWDP_TILE_DBG & 32) return (v8i){1, 2, 3, 4, 5, 6, 7, 8};
+      return cat8(*(const v4i*)(pb0 + t * kTileBytes), *(const v4i*)(pb1 + t * kTileBytes));
+    };
+    auto read_s = [&](int t) __attribute__((always_inline)) { return (DWDP_TILE_DBG & 32) ? 1.f : ps[t * 64]; };
+    auto mul = [&](int t, const v8i& bf, v4f& p0, v4f& p1) __attribute__((always_inline)) {
+      if (DWDP_TILE_DBG & 1) return;
+      if (DWDP_TILE_DBG & 64) {
+        acc[0][t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af0, bf, acc[0][t], 0, 0, 0, 0, 0, 0);
+        acc[1][t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af1, bf, acc[1][t], 0, 0, 0, 0, 0, 0);
+      } else {
+        p0 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af0, bf, zero, 0, 0, 0, 0, 0, 0);
+        p1 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af1, bf, zero, 0, 0, 0, 0, 0, 0);
       }
     };
-    auto tile = [&](int t, const v8i& bf, v8i& bf_n, v4f& p0, v4f& p1, float& sa, const v4f& q0, const v4f& q1,
-                    float sa_prev) {
-      if (t < ntt && !(DWDP_TILE_DBG & 1)) {
-        if (!(DWDP_TILE_DBG & 32)) {
-          if (t + 1 < kTT)  // tile t+1 is always inside the LDS image
-            bf_n = cat8(*(const v4i*)(pb0 + (t + 1) * kTileBytes), *(const v4i*)(pb1 + (t + 1) * kTileBytes));
-          sa = ps[t * 64];
-        }
-        if (DWDP_TILE_DBG & 64) {
-          acc[0][t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af0, bf, acc[0][t], 0, 0, 0, 0, 0, 0);
-          acc[1][t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af1, bf, acc[1][t], 0, 0, 0, 0, 0, 0);
-        } else {
-          p0 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af0, bf, zero, 0, 0, 0, 0, 0, 0);
-          p1 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af1, bf, zero, 0, 0, 0, 0, 0, 0);
-        }
-      }
-      fold(t - 1, q0, q1, sa_prev);
-      // operation i goes after tile op_slot(i) (always, also past ntt)
+    auto fold = [&](int t, const v4f& p0, const v4f& p1, float sa) __attribute__((always_inline)) {
+      if (DWDP_TILE_DBG & (1 | 64)) return;
+      // timing experiment 2048: no scale products (wrong results)
+      const float s0 = (DWDP_TILE_DBG & 2048) ? sa : sa * w0;
+      const float s1 = (!G1 || (DWDP_TILE_DBG & 2048)) ? s0 : sa * w1;  // GEMM-2: both tiles lie in one scale block
+      // whole-vector read and write of the accumulator: element-wise stores into it under
+      // nested conditions keep the compiler from holding the array in registers
+      v4f a0v = acc[0][t], a1v = acc[1][t];
+#pragma unroll
+      for (int i = 0; i < 4; i++) a0v[i] = fmaf(p0[i], s0, a0v[i]);
+#pragma unroll
+      for (int i = 0; i < 4; i++) a1v[i] = fmaf(p1[i], s1, a1v[i]);
+      acc[0][t] = a0v;
+      acc[1][t] = a1v;
+    };
+    // operations of the next fetch that follow tile t / that have not been issued before tile t
+    auto ops_at = [&](int t) __attribute__((always_inline)) {
 #pragma unroll
       for (int op = 0; op < kVmemPerStep; op++)
         if (op_slot(op) == t && (op != kBP || kNextHasScales)) issue_op(op, pos_n, lbn, an);
-      __builtin_amdgcn_sched_barrier(0);
     };
+    // Token tiles in pairs behind one wave-uniform branch per pair (a pair past the expert's
+    // last row only settles the scaling still pending); the operations of the next fetch are
+    // issued between the pairs, whether or not they were multiplied.  With an odd tile count
+    // the last pair multiplies one tile of repeated rows.
+    // Per tile t, in program order: issue the LDS read of tile t+1's operand, multiply tile t
+    // (its operand was requested one tile ago), scale tile t-1's products, then request tile
+    // t+1's activation scale into the register that scaling has just released.  LDS reads
+    // return in order, so each use waits exactly until its own read has landed and never for
+    // the younger ones.
+    // issue order inside a tile: operand reads, then each MFMA followed by the five VALU
+    // operations that scale the older products of the same weight tile, then the scale read
+    auto tile_order = []() __attribute__((always_inline)) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // LDS reads (operand, kBDepth tiles ahead)
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);  // VALU
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    };
+    int ntt_v = ntt;
+    asm volatile("" : "+s"(ntt_v));  // compared afresh in every block: the comparisons stay scalar compares
 #pragma unroll
-    for (int t = 0; t < kTT; t += 2) {
-      tile(t, bfx, bfy, px0, px1, sax, py0, py1, say);
-      tile(t + 1, bfy, bfx, py0, py1, say, px0, px1, sax);
-    }
-    fold(kTT - 1, py0, py1, say);
+    for (int t = 0; t < kBDepth; t++) bf[t] = read_b(t);
+    sa[0] = read_s(0);
+    auto tile = [&](auto t_const) __attribute__((always_inline)) {
+      constexpr int t = decltype(t_const)::value;
+      if constexpr (t + kBDepth < kTT) bf[(t + kBDepth) % (kBDepth + 1)] = read_b(t + kBDepth);
+      mul(t, bf[t % (kBDepth + 1)], p0[t % 2], p1[t % 2]);
+      if constexpr (t > 0) fold(t - 1, p0[(t - 1) % 2], p1[(t - 1) % 2], sa[(t - 1) % 2]);
+      if constexpr (t + 1 < kTT) sa[(t + 1) % 2] = read_s(t + 1);
+      tile_order();
+    };
+    static_for<kTT / 2>([&](auto pair_const) __attribute__((always_inline)) {
+      constexpr int t = 2 * decltype(pair_const)::value;
+      if (t < ntt_v) {
+        tile(std::integral_constant<int, t>{});
+        __builtin_amdgcn_sched_barrier(0);
+        tile(std::integral_constant<int, t + 1>{});
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      ops_at(t);
+      ops_at(t + 1);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // the scaling still pending after the last pair that was multiplied
+    static_for<kTT / 2>([&](auto pair_const) __attribute__((always_inline)) {
+      constexpr int t = 2 * decltype(pair_const)::value + 2;
+      if (t - 2 < ntt_v && t >= ntt_v) fold(t - 1, p0[1], p1[1], sa[1]);
+    });
+    const int kn = min(kb + 1, nkb - 1);
+    wc0 = *(cf32)(sw[0] + kn);
+    wc1 = *(cf32)(sw[1] + kn);
   };
   static_assert(kTT / 2 >= kVmemPerStep - 1 && kTT % 2 == 0, "every operation has a tile to follow");
 
@@ -320,7 +401,7 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
     // pinned between scheduling barriers: nothing of the following issue (its address
     // arithmetic reuses registers of retired loads) may move above the wait
     __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(wait_vm(decltype(n_next)::value));
+    __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(decltype(n_next)::value));
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
   };
@@ -355,6 +436,10 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   keep(a2);
   __builtin_amdgcn_sched_barrier(0);
   __syncthreads();
+  if ((DWDP_TILE_DBG & 1024) && threadIdx.x == 0 && (blockIdx.x == 0 || blockIdx.x == 1001)) {
+    const long long dc = clock64() - dbg_c0, dw = wall_clock64() - dbg_w0;
+    printf("tile kernel G1=%d block %d: %lld cycles, %lld ticks of 10 ns -> %.0f MHz, %d K blocks\n", (int)G1, (int)blockIdx.x, dc, dw, (double)dc / (double)dw * 100.0, nkb);
+  }
 
   if (G1) {
     const int njb = I / 128;
