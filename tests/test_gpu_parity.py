@@ -208,6 +208,19 @@ def test_layer_fp8_long_k(binding, H, I, T, smr):
     _layer_case(binding, cfg, x, logits, None, w, check_intermediates=True, stream_max_rows=smr)
 
 
+@pytest.mark.parametrize("T", [31, 32, 33, 64, 287, 288, 289, 320, 577])
+def test_layer_fp8_tile_boundaries(binding, T):
+    """Row counts at the edges of the LDS-tiled kernel's units (32-token tiles of the matrix
+    instruction, 288-token workgroup tiles): the shared expert holds exactly T rows, the routed
+    experts ragged shares of 2T, every expert on the tiled kernels."""
+    print("layer fp8 tile boundaries T", T, flush=True)
+    cfg = inputs.small_fp8_layer(T=T, H=256, I=128, E=8, K=2, n_group=1, topk_group=1)
+    x = inputs.make_activations(cfg, 100 + T)
+    logits = inputs.make_gate_logits(cfg, x, 100 + T)
+    w = inputs.make_expert_weights(cfg, 100 + T)
+    _layer_case(binding, cfg, x, logits, None, w, check_intermediates=True, stream_max_rows=0)
+
+
 def test_layer_small_fp8_no_shared_and_empty(binding):
     print("layer small fp8 no shared / T=0", flush=True)
     cfg = inputs.small_fp8_layer(T=40, has_shared=0, E=32, n_group=4, topk_group=2, K=4, H=384, I=128)
