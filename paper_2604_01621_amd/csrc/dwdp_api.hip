@@ -140,7 +140,7 @@ extern "C" dwdp_status dwdp_create(const dwdp_config* cfg, void* compute_stream,
   hipError_t e = hipGetDevice(&c->device);
   for (int i = 0; i < DWDP_N_WS && e == hipSuccess; i++)
     if (bytes[i]) e = hipMalloc(&c->ws[i], bytes[i]);
-  const int chunk = permute_chunk_tokens(cfg->E);
+  const int chunk = permute_multi_chunk_tokens(cfg->E);
   const size_t n_chunks = (T + chunk - 1) / chunk;
   if (e == hipSuccess) e = hipMalloc((void**)&c->chunk_counts, n_chunks * E * 4);
   c->mt_cap = tile_mtiles_cap((int)c->rows_max, c->n_slots, 0);

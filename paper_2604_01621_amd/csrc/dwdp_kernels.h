@@ -24,6 +24,8 @@ struct RouteParams {
 
 // Tokens per permutation chunk for E experts (bitmask of E x chunk bits must fit 48 KiB of LDS).
 int permute_chunk_tokens(int E);
+// Tokens per workgroup of the multi-workgroup permutation (sizes the chunk_counts scratch).
+int permute_multi_chunk_tokens(int E);
 
 void launch_route(const float* logits, const float* bias, int T, const RouteParams& p, int32_t* ids, float* w,
                   hipStream_t stream);

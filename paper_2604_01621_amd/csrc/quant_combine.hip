@@ -41,9 +41,9 @@ __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ y
   const int n = K + (has_shared ? 1 : 0);
   for (int c = threadIdx.x * 8; c < H; c += blockDim.x * 8) {
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int k = 0; k < n; k++) {
-      const float wk = w_s[k];
-      if (YP32) {
+    if (YP32) {
+      for (int k = 0; k < n; k++) {
+        const float wk = w_s[k];
         const float* p = (const float*)yp_ + (size_t)row_s[k] * H + c;
         const v4f a = *(const v4f*)p;
         const v4f b = *(const v4f*)(p + 4);
@@ -52,13 +52,28 @@ __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ y
           acc[i] = fmaf(wk, a[i], acc[i]);
           acc[4 + i] = fmaf(wk, b[i], acc[4 + i]);
         }
-      } else {
-        const v4i raw = *(const v4i*)((const uint16_t*)yp_ + (size_t)row_s[k] * H + c);
+      }
+    } else {
+      // rows in groups of kG: all loads of a group are issued before the first is used (the
+      // rows of a token lie far apart, one load at a time leaves the lane waiting on each);
+      // the adds keep the order k = 0..n-1.  Slots past n re-read the last row and are not added.
+      constexpr int kG = 5;
+      for (int k0 = 0; k0 < n; k0 += kG) {
+        v4i raw[kG];
 #pragma unroll
-        for (int i = 0; i < 4; i++) {
-          uint32_t u = (uint32_t)raw[i];
-          acc[2 * i] = fmaf(wk, __uint_as_float(u << 16), acc[2 * i]);
-          acc[2 * i + 1] = fmaf(wk, __uint_as_float(u & 0xFFFF0000u), acc[2 * i + 1]);
+        for (int j = 0; j < kG; j++)
+          raw[j] = *(const v4i*)((const uint16_t*)yp_ + (size_t)row_s[min(k0 + j, n - 1)] * H + c);
+#pragma unroll
+        for (int j = 0; j < kG; j++) {
+          if (k0 + j < n) {
+            const float wk = w_s[k0 + j];
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+              uint32_t u = (uint32_t)raw[j][i];
+              acc[2 * i] = fmaf(wk, __uint_as_float(u << 16), acc[2 * i]);
+              acc[2 * i + 1] = fmaf(wk, __uint_as_float(u & 0xFFFF0000u), acc[2 * i + 1]);
+            }
+          }
         }
       }
     }

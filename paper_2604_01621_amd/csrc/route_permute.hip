@@ -172,6 +172,14 @@ int permute_chunk_tokens(int E) {
   return ch;
 }
 
+// Tokens per workgroup when the permutation runs on several workgroups (T > permute_chunk_tokens):
+// small chunks, so that a long token list spreads over many CUs (8192 tokens: 64 workgroups) and
+// the rank of a token inside its chunk is a few population counts.
+int permute_multi_chunk_tokens(int E) {
+  const int ch = permute_chunk_tokens(E);
+  return ch < 128 ? ch : 128;
+}
+
 // Build the [E x wpe] bitmask of tokens [t0, t0+nt) in LDS.
 __device__ __forceinline__ void build_mask(uint32_t* mask, const int32_t* __restrict__ ids, int t0, int nt, int E,
                                            int K, int wpe) {
@@ -313,15 +321,16 @@ void launch_permute(const int32_t* ids, int T, int E, int K, int has_shared, int
     hipLaunchKernelGGL(permute_empty_kernel, dim3((n_off + 255) / 256), dim3(256), 0, stream, offsets, n_off);
     return;
   }
-  const int chunk = permute_chunk_tokens(E);
-  const int wpe = chunk / 32;
-  const size_t mask_bytes = (size_t)E * wpe * sizeof(uint32_t);
-  if (T <= chunk) {
-    size_t lds = mask_bytes + (kPermThreads + E + 1) * sizeof(int32_t);
+  if (T <= permute_chunk_tokens(E)) {
+    const int wpe = permute_chunk_tokens(E) / 32;
+    size_t lds = (size_t)E * wpe * sizeof(uint32_t) + (kPermThreads + E + 1) * sizeof(int32_t);
     hipLaunchKernelGGL(permute_single_kernel, dim3(1), dim3(kPermThreads), lds, stream, ids, T, E, K, has_shared, wpe,
                        offsets, perm, inv_perm, list, stream_max_rows);
     return;
   }
+  const int chunk = permute_multi_chunk_tokens(E);
+  const int wpe = chunk / 32;
+  const size_t mask_bytes = (size_t)E * wpe * sizeof(uint32_t);
   const int n_chunks = (T + chunk - 1) / chunk;
   hipLaunchKernelGGL(permute_count_kernel, dim3(n_chunks), dim3(kPermThreads), mask_bytes, stream, ids, T, E, K, chunk,
                      wpe, chunk_counts);
