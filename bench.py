@@ -156,7 +156,7 @@ def main():
         b2 = cfg.H * cfg.I * el + (4 * (cfg.H // 128) * (cfg.I // 128) if fp8 else 0)
     # which kernel family serves which expert (the library's default threshold: 16 rows)
     smr = args.stream_max_rows if args.stream_max_rows is not None else 16
-    if not fp8 or cfg.T <= smr:
+    if not (fp8 or mx) or cfg.T <= smr:
         smr = 1 << 30
     n_stream = int(((counts > 0) & (counts <= smr)).sum())
     n_tile = int((counts > smr).sum())

@@ -155,8 +155,7 @@ dwdp_status dwdp_prefetch_layer(dwdp_ctx* ctx, int32_t layer, const void* const*
                                 const size_t* bytes, int32_t n_peers, int32_t n_params, size_t slice_bytes);
 
 /*
- * Kernel selection of the FP8 grouped GEMM (MXFP4 weights always use their weight-streaming
- * kernels).  Experts with 1..max_rows sorted rows are
+ * Kernel selection of the FP8 / MXFP4 grouped GEMM.  Experts with 1..max_rows sorted rows are
  * computed by the weight-streaming kernels (weights straight to registers, 16 token rows per
  * pass over the weights), experts with more rows by the LDS-tiled kernels (288-token tiles,
  * weights read once per tile).  Default 16.  0 sends every

@@ -290,11 +290,11 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
   const bool mx = c.w_dtype == DWDP_W_MXFP4;
   const bool fp8 = c.w_dtype != DWDP_W_BF16;  // FP8 activations and intermediates (FP8 and MXFP4 weights)
   // Experts with 1..smr rows stream their weights; the others go through the LDS-tiled kernel
-  // (FP8 weights only: MXFP4 weights always stream).
+  // (FP8 and MXFP4 weights).
   const int rows = T * c.K + (c.has_shared ? T : 0);
   const int smr = ctx->stream_max_rows;
-  const bool use_tile = fp8 && !mx && T > smr;  // an expert holds at most T rows
-  const bool use_stream = mx || smr > 0;
+  const bool use_tile = fp8 && T > smr;  // an expert holds at most T rows
+  const bool use_stream = smr > 0;
   TileSched ts{ctx->mt_expert, ctx->mt_row0, ctx->n_mtiles, 0};
   if (use_tile) ts.n_mt_max = tile_mtiles_cap(rows, ctx->n_slots, smr);
   // Two launches prepare the GEMMs: routing with the (independent) activation quantisation
@@ -328,14 +328,14 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
     if (use_stream) {
       if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM1), sc));
       if (mx)
-        launch_gemm1_mx(ga, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
+        launch_gemm1_mx(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
                         (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], sc);
       else
         launch_gemm1_fp8(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
                          (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], sc);
       if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM2), sc));
       if (mx)
-        launch_gemm2_mx(ga, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
+        launch_gemm2_mx(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
                         ctx->ws[DWDP_WS_YP], sc);
       else
         launch_gemm2_fp8(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
@@ -349,10 +349,10 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
     }
     if (use_tile) {
       if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfMain + 1), s));
-      launch_gemm1_fp8_tile(ga, ts, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
+      launch_gemm1_fp8_tile(ga, ts, mx, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
                             (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], s);
       if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfMain + 2), s));
-      launch_gemm2_fp8_tile(ga, ts, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
+      launch_gemm2_fp8_tile(ga, ts, mx, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
                             ctx->ws[DWDP_WS_YP], s);
       if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfMain + 3), s));
     }

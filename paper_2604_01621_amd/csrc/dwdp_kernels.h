@@ -82,17 +82,19 @@ void launch_pack_fp8_tiles(const void* src, void* dst, long rows, int cols, hipS
 // Streaming kernels: experts with 1..max_rows rows.  LDS-tiled kernels: the experts in the tile list.
 void launch_gemm1_fp8(const GemmArgs& a, int max_rows, const uint8_t* xq, const float* xs, uint8_t* hq, float* hs,
                       hipStream_t stream);
-void launch_gemm1_fp8_tile(const GemmArgs& a, const TileSched& ts, const uint8_t* xq, const float* xs, uint8_t* hq,
-                           float* hs, hipStream_t stream);
+// mxfp4: the listed experts' weights are MXFP4 (launch_pack_mxfp4 layouts) instead of FP8
+void launch_gemm1_fp8_tile(const GemmArgs& a, const TileSched& ts, bool mxfp4, const uint8_t* xq, const float* xs,
+                           uint8_t* hq, float* hs, hipStream_t stream);
 // FP8: yp = Hq W2^T, bf16 [rows,H]
 void launch_gemm2_fp8(const GemmArgs& a, int max_rows, const uint8_t* hq, const float* hs, void* yp,
                       hipStream_t stream);
-void launch_gemm2_fp8_tile(const GemmArgs& a, const TileSched& ts, const uint8_t* hq, const float* hs, void* yp,
-                           hipStream_t stream);
+void launch_gemm2_fp8_tile(const GemmArgs& a, const TileSched& ts, bool mxfp4, const uint8_t* hq, const float* hs,
+                           void* yp, hipStream_t stream);
 // MXFP4 weights (layouts of launch_pack_mxfp4), FP8 activations: same results as the FP8 pair above
-void launch_gemm1_mx(const GemmArgs& a, const uint8_t* xq, const float* xs, uint8_t* hq, float* hs,
+void launch_gemm1_mx(const GemmArgs& a, int max_rows, const uint8_t* xq, const float* xs, uint8_t* hq, float* hs,
                      hipStream_t stream);
-void launch_gemm2_mx(const GemmArgs& a, const uint8_t* hq, const float* hs, void* yp, hipStream_t stream);
+void launch_gemm2_mx(const GemmArgs& a, int max_rows, const uint8_t* hq, const float* hs, void* yp,
+                     hipStream_t stream);
 // Row-major packed E2M1 codes [rows, cols/2] and E8M0 scales [rows, cols/32] -> the streaming layouts.
 void launch_pack_mxfp4(const void* codes, const void* scales, void* codes_out, void* scales_out, long rows, int cols,
                        hipStream_t stream);

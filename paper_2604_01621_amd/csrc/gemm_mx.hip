@@ -122,14 +122,14 @@ __device__ __forceinline__ void mx_mainloop(const uint8_t* const (&wt)[NT], cons
 __global__ __launch_bounds__(kMxThreads, 2) void gemm1_mx_stream_kernel(
     const dwdp_expert_ptrs* __restrict__ table, const int32_t* __restrict__ offsets, const int32_t* __restrict__ perm,
     const uint8_t* __restrict__ xq, const float* __restrict__ xs, uint8_t* __restrict__ hq, float* __restrict__ hs,
-    int E, int T, int H, int I, int K) {
+    int E, int T, int H, int I, int K, int max_rows) {
   __shared__ float amax_s[4][16];
   const int njb = I / 128;
   const int e = blockIdx.x / njb;
   const int jb = blockIdx.x - e * njb;
   const int r0 = offsets[e];
   const int r1 = offsets[e + 1];
-  if (r1 <= r0) return;  // no tokens: weights never touched
+  if (r1 <= r0 || r1 - r0 > max_rows) return;  // no tokens: weights never touched; many: tiled kernel
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 15, lq = lane >> 4;
   const int nkb = H / 128;
   const int ng = (nkb + 3) >> 2;
@@ -188,13 +188,13 @@ constexpr int kMxG2Tiles = 2;
 constexpr int kMxG2Rows = 4 * kMxG2Tiles * 16;
 __global__ __launch_bounds__(kMxThreads, 2) void gemm2_mx_stream_kernel(
     const dwdp_expert_ptrs* __restrict__ table, const int32_t* __restrict__ offsets, const uint8_t* __restrict__ hq,
-    const float* __restrict__ hs, uint16_t* __restrict__ yp, int H, int I) {
+    const float* __restrict__ hs, uint16_t* __restrict__ yp, int H, int I, int max_rows) {
   const int nnb = H / kMxG2Rows;  // H is a multiple of 128
   const int e = blockIdx.x / nnb;
   const int nb = blockIdx.x - e * nnb;
   const int r0 = offsets[e];
   const int r1 = offsets[e + 1];
-  if (r1 <= r0) return;
+  if (r1 <= r0 || r1 - r0 > max_rows) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane & 15, lq = lane >> 4;
   const int nkb = I / 128;
   const int ng = (nkb + 3) >> 2;
@@ -229,17 +229,18 @@ __global__ __launch_bounds__(kMxThreads, 2) void gemm2_mx_stream_kernel(
   }
 }
 
-void launch_gemm1_mx(const GemmArgs& a, const uint8_t* xq, const float* xs, uint8_t* hq, float* hs,
+void launch_gemm1_mx(const GemmArgs& a, int max_rows, const uint8_t* xq, const float* xs, uint8_t* hq, float* hs,
                      hipStream_t stream) {
   if (a.T <= 0) return;
   hipLaunchKernelGGL(gemm1_mx_stream_kernel, dim3(a.n_slots * (a.I / 128)), dim3(kMxThreads), 0, stream, a.table,
-                     a.offsets, a.perm, xq, xs, hq, hs, a.E, a.T, a.H, a.I, a.K);
+                     a.offsets, a.perm, xq, xs, hq, hs, a.E, a.T, a.H, a.I, a.K, max_rows);
 }
 
-void launch_gemm2_mx(const GemmArgs& a, const uint8_t* hq, const float* hs, void* yp, hipStream_t stream) {
+void launch_gemm2_mx(const GemmArgs& a, int max_rows, const uint8_t* hq, const float* hs, void* yp,
+                     hipStream_t stream) {
   if (a.T <= 0) return;
   hipLaunchKernelGGL(gemm2_mx_stream_kernel, dim3(a.n_slots * (a.H / kMxG2Rows)), dim3(kMxThreads), 0, stream,
-                     a.table, a.offsets, hq, hs, (uint16_t*)yp, a.H, a.I);
+                     a.table, a.offsets, hq, hs, (uint16_t*)yp, a.H, a.I, max_rows);
 }
 
 // Row-major packed codes [rows, cols/2] -> tile-major.  One thread per 16-byte piece of dst.

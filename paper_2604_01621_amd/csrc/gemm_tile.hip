@@ -131,11 +131,17 @@ __device__ __forceinline__ void static_for(F&& f) {
 // The 32 weight rows of a wave for one K block in the operand layout of the 32x32x64
 // instruction: t[c][h] = this lane's bytes 16h..16h+15 of the 32 it feeds to the instruction
 // of the block's 64-wide half c (16 registers in all).
+// MXFP4 weights: t[0][c] = the 32 four-bit elements of half c (16 bytes), s[c] = the dword
+// whose byte (K block % 4) is their E8M0 scale; t[1][*] unused.
 struct AFrag {
   v4i t[2][2];
+  int s[2];
 };
 
-template <bool G1>
+// MX = false: FP8 e4m3 weights (packed 2 KiB tiles, fp32 scale per 128x128 block, applied by the
+// VALU scaling).  MX = true: MXFP4 weights (packed 1 KiB tiles of E2M1 codes, one E8M0 scale per
+// 32 along K, applied by the matrix instruction itself), FP8 activations as before.
+template <bool G1, bool MX>
 __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
     const dwdp_expert_ptrs* __restrict__ table, const int32_t* __restrict__ offsets, const int32_t* __restrict__ perm,
     const int32_t* __restrict__ mt_expert, const int32_t* __restrict__ mt_row0, const int32_t* __restrict__ n_mtiles,
@@ -187,8 +193,10 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   // ---- sources, fixed over the K loop ----
   // weights: this wave's two packed 16-row tiles (G1: gate tile and up tile of 16 h columns;
   // GEMM-2: 32 consecutive rows).  Rows 0..15 of the A operand are tile 0, rows 16..31 tile 1.
+  constexpr int kABytes = MX ? 1024 : kTileBytes;  // one packed 16-row tile of one K block
   const uint8_t* a_src[2];
   const float* sw[2];
+  const uint8_t* ms_src[2];
 #pragma unroll
   for (int j = 0; j < 2; j++) {
     int tr;
@@ -198,14 +206,19 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
       tr = min(panel * 16 + wave * 2 + j, n_tile_rows - 1);
     if (DWDP_TILE_DBG & 512) tr = G1 ? (j == 0 ? 0 : I / 16) + wave : wave * 2 + j;  // every workgroup reads panel 0
     a_src[j] = ((DWDP_TILE_DBG & 512) ? (const uint8_t*)(G1 ? table[0].w13 : table[0].w2) : wbase) +
-               (size_t)tr * nkb * kTileBytes;  // wave-uniform
-    sw[j] = sbase + (size_t)(tr / 8) * nkb;  // 8 tiles of 16 rows per 128-row scale block
+               (size_t)tr * nkb * kABytes;  // wave-uniform
+    sw[j] = sbase + (size_t)(tr / 8) * nkb;  // 8 tiles of 16 rows per 128-row scale block (FP8 weights)
+    ms_src[j] = (const uint8_t*)sbase + (size_t)tr * ((nkb + 3) >> 2) * 256;  // packed E8M0 scales (MXFP4 weights)
   }
   // Inside a packed tile, byte half*1024 + (q*16 + r)*16 + b is element (row r, column
   // 32q + 16*half + b).  The instruction of half c wants from lane (ln, lg) the 32 columns
   // 64c + 32lg .. +31 of row ln: q = 2c + lg, both 16-byte halves.  One load per (c, half)
   // with a per-lane offset (tile 1 lies a fixed distance behind tile 0) and an immediate.
+  // MXFP4: a packed tile holds at (q*16 + r)*16 the 32 elements 32q..32q+31 of row r, and the scale
+  // group of four K blocks holds at (q*16 + r)*4 their four scale bytes: the same lane offsets
+  // with 16 and 4 bytes per lane, half c at +512 and +128.
   const uint32_t a_voff = (uint32_t)((ln >> 4) ? (a_src[1] - a_src[0]) : 0) + (uint32_t)((lg * 16 + (ln & 15)) * 16);
+  const uint32_t ms_voff = (uint32_t)((ln >> 4) ? (ms_src[1] - ms_src[0]) : 0) + (uint32_t)((lg * 16 + (ln & 15)) * 4);
   // tokens: the source row of every token slot of the tile (slots past the end repeat the last row)
   for (int i = tid; i < kSaLen; i += kTileThreads) {
     const int row = min(r0 + i, r_end - 1);
@@ -230,7 +243,12 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   }
   // operand reads: byte offset of chunk 2lg of row ln inside a 32-token tile; chunk 2lg+1 is
   // at ^16, the chunks of the second half of the K block at ^64
-  const int b_rd0 = ln * 128 + (((2 * lg) ^ swz(ln)) << 4);
+  // With an FP4 A operand the instruction pairs K elements by position, and the position of an
+  // 8-bit operand's bytes is registers 0..3 = bytes 16lg..16lg+15 and registers 4..7 = bytes
+  // 32+16lg.. of the 64 (measured with single-element probes); with two 8-bit operands any order
+  // both share works, and the contiguous one is used.
+  constexpr int kBSecond = MX ? 32 : 16;  // address XOR from a lane's first 16 bytes to its second
+  const int b_rd0 = ln * 128 + (((MX ? lg : 2 * lg) ^ swz(ln)) << 4);
   const uint32_t sa_src = (uint32_t)lds_row[wave * 64 + lane] * nkb;
   // LDS byte offsets of the copy targets (wave-uniform, kept in scalar registers)
   auto uniform = [](uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); };
@@ -268,16 +286,29 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
     } else if (op == kBP) {
       if (!(DWDP_TILE_DBG & 8)) dma12(act_s + (sa_src + (uint32_t)kb), sg_off[(pos / 3) & 1]);
     } else if (!(DWDP_TILE_DBG & 4)) {
-      const int w = op - kBP - 1;  // 0..3 = (c, half)
-      const uint8_t* base = a_src[0] + (size_t)kb * kTileBytes;  // wave-uniform: scalar registers
-      if (w == 0)
-        asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "+v"(a.t[0][0]) : "v"(a_voff), "s"(base));
-      else if (w == 1)
-        asm volatile("global_load_dwordx4 %0, %1, %2 offset:1024 nt" : "+v"(a.t[0][1]) : "v"(a_voff), "s"(base));
-      else if (w == 2)
-        asm volatile("global_load_dwordx4 %0, %1, %2 offset:512 nt" : "+v"(a.t[1][0]) : "v"(a_voff), "s"(base));
-      else
-        asm volatile("global_load_dwordx4 %0, %1, %2 offset:1536 nt" : "+v"(a.t[1][1]) : "v"(a_voff), "s"(base));
+      const int w = op - kBP - 1;  // FP8: 0..3 = (c, half); MXFP4: codes of half 0, half 1, scales of half 0, half 1
+      if (!MX) {
+        const uint8_t* base = a_src[0] + (size_t)kb * kABytes;  // wave-uniform: scalar registers
+        if (w == 0)
+          asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "+v"(a.t[0][0]) : "v"(a_voff), "s"(base));
+        else if (w == 1)
+          asm volatile("global_load_dwordx4 %0, %1, %2 offset:1024 nt" : "+v"(a.t[0][1]) : "v"(a_voff), "s"(base));
+        else if (w == 2)
+          asm volatile("global_load_dwordx4 %0, %1, %2 offset:512 nt" : "+v"(a.t[1][0]) : "v"(a_voff), "s"(base));
+        else
+          asm volatile("global_load_dwordx4 %0, %1, %2 offset:1536 nt" : "+v"(a.t[1][1]) : "v"(a_voff), "s"(base));
+      } else {
+        const uint8_t* base = a_src[0] + (size_t)kb * kABytes;
+        const uint8_t* sbase_kb = ms_src[0] + (size_t)(kb >> 2) * 256;
+        if (w == 0)
+          asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "+v"(a.t[0][0]) : "v"(a_voff), "s"(base));
+        else if (w == 1)
+          asm volatile("global_load_dwordx4 %0, %1, %2 offset:512 nt" : "+v"(a.t[0][1]) : "v"(a_voff), "s"(base));
+        else if (w == 2)
+          asm volatile("global_load_dword %0, %1, %2" : "+v"(a.s[0]) : "v"(ms_voff), "s"(sbase_kb));
+        else
+          asm volatile("global_load_dword %0, %1, %2 offset:128" : "+v"(a.s[1]) : "v"(ms_voff), "s"(sbase_kb));
+      }
     }
   };
   // the whole fetch of position pos (prologue)
@@ -290,7 +321,7 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   // Weight scales of the block about to be multiplied: scalar loads issued at the end of the
   // previous block's multiply and waited for in publish(), so that no scalar load is pending
   // while LDS reads are in flight.
-  float wc0 = *(cf32)(sw[0]), wc1 = *(cf32)(sw[1]);
+  float wc0 = MX ? 1.f : *(cf32)(sw[0]), wc1 = MX ? 1.f : *(cf32)(sw[1]);
   // Multiply block kb from (image IMG, a) and, spread between its token tiles, issue the
   // fetch of position kb + 2 into (image IMGN, an): issued in one burst the operations keep
   // the wave at the memory pipeline's door for as long as the transfers take, one per tile
@@ -304,11 +335,20 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
     constexpr bool kNextHasScales = (C + 2) % 3 == 0;
     const int pos_n = kb + 2;
     const float w0 = wc0, w1 = wc1;
-    const v8i af0 = cat8(a.t[0][0], a.t[0][1]);
-    const v8i af1 = cat8(a.t[1][0], a.t[1][1]);
+    const v4i zero4 = {0, 0, 0, 0};
+    const v8i af0 = MX ? cat8(a.t[0][0], zero4) : cat8(a.t[0][0], a.t[0][1]);
+    const v8i af1 = MX ? cat8(a.t[0][1], zero4) : cat8(a.t[1][0], a.t[1][1]);
+    // MXFP4: this block's scale byte moved to byte 0 of the scale operand
+    const int ms0 = MX ? (int)((uint32_t)a.s[0] >> (8 * (kb & 3))) : 0;
+    const int ms1 = MX ? (int)((uint32_t)a.s[1] >> (8 * (kb & 3))) : 0;
+    // cbsz 4: A is FP4 E2M1; blgp 0: B is FP8 E4M3; A scale = byte 0 of ms; B scale 127 = 1.0
+    auto mfma = [&](const v8i& af, const v8i& bf, const v16f& c, int ms) __attribute__((always_inline)) -> v16f {
+      if (MX) return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(af, bf, c, 4, 0, 0, ms, 0, 0x7f7f7f7f);
+      return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(af, bf, c, 0, 0, 0, 0, 0, 0);
+    };
     const uint8_t* lb = IMG == 0 ? lds_b0 : (IMG == 1 ? lds_b1 : lds_b2);
     const uint8_t* pb00 = lb + b_rd0;         // half 0 of the block, bytes 0..15 of the lane's 32
-    const uint8_t* pb01 = lb + (b_rd0 ^ 16);  //                      bytes 16..31
+    const uint8_t* pb01 = lb + (b_rd0 ^ kBSecond);  //                the lane's second 16 bytes
     const uint32_t ab0 = lds_offset(pb00), ab1 = lds_offset(pb01);
     const float* ps = (((kb / 3) & 1) ? lds_sg1 : lds_sg0) + ln * 4 + C;
     v16f zero;
@@ -332,8 +372,12 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
     };
     auto read_s = [&](int t) __attribute__((always_inline)) { return ps[t * 128]; };
     auto scale_products = [&](float sa_t, float& s0, float& s1) __attribute__((always_inline)) {
-      s0 = sa_t * w0;
-      s1 = G1 ? sa_t * w1 : s0;  // GEMM-2: the 32 rows lie in one scale block
+      if (MX) {
+        s0 = s1 = sa_t;  // the weight scales were applied inside the instruction
+      } else {
+        s0 = sa_t * w0;
+        s1 = G1 ? sa_t * w1 : s0;  // GEMM-2: the 32 rows lie in one scale block
+      }
     };
     // acc[t] += products * scale: rows 0..15 of the A operand (registers 0..7) with s0, rows
     // 16..31 with s1.  Whole-vector read and write of the accumulator: element-wise stores
@@ -371,9 +415,9 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
     auto tile = [&](auto t_const) __attribute__((always_inline)) {
       constexpr int t = decltype(t_const)::value;
       bq[1] = read_b(t, 1);
-      if (!(DWDP_TILE_DBG & 1)) pr = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(af0, bq[0], zero, 0, 0, 0, 0, 0, 0);
+      if (!(DWDP_TILE_DBG & 1)) pr = mfma(af0, bq[0], zero, ms0);
       if constexpr (t + 1 < kTT) bq[0] = read_b(t + 1, 0);
-      if (!(DWDP_TILE_DBG & 1)) pr = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(af1, bq[1], pr, 0, 0, 0, 0, 0, 0);
+      if (!(DWDP_TILE_DBG & 1)) pr = mfma(af1, bq[1], pr, ms1);
       scale_products(sa[t % 2], sp0, sp1);
       fold(t, pr, sp0, sp1);
       if constexpr (t + 2 < kTT) sa[t % 2] = read_s(t + 2);
@@ -386,9 +430,11 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
       ops_at(t);
       __builtin_amdgcn_sched_barrier(0);
     });
-    const int kn = min(kb + 1, nkb - 1);
-    wc0 = *(cf32)(sw[0] + kn);
-    wc1 = *(cf32)(sw[1] + kn);
+    if (!MX) {
+      const int kn = min(kb + 1, nkb - 1);
+      wc0 = *(cf32)(sw[0] + kn);
+      wc1 = *(cf32)(sw[1] + kn);
+    }
   };
   static_assert(kTT >= kVmemPerStep - 1, "every operation has a tile to follow");
 
@@ -413,7 +459,7 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   };
 
   auto keep = [](const AFrag& a) {
-    asm volatile("" ::"v"(a.t[0][0]), "v"(a.t[0][1]), "v"(a.t[1][0]), "v"(a.t[1][1]));
+    asm volatile("" ::"v"(a.t[0][0]), "v"(a.t[0][1]), "v"(a.t[1][0]), "v"(a.t[1][1]), "v"(a.s[0]), "v"(a.s[1]));
   };
   AFrag a0 = {}, a1 = {}, a2 = {};
   if (DWDP_TILE_DBG & (4 | 128)) {  // timing experiments without weight loads: operands the compiler cannot fold
@@ -541,22 +587,23 @@ int tile_mtiles_cap(int rows, int n_slots, int stream_max_rows) {
   return rows / kBM + (int)(by_rows < n_slots ? by_rows : n_slots) + 1;
 }
 
-void launch_gemm1_fp8_tile(const GemmArgs& a, const TileSched& ts, const uint8_t* xq, const float* xs, uint8_t* hq,
-                           float* hs, hipStream_t stream) {
+void launch_gemm1_fp8_tile(const GemmArgs& a, const TileSched& ts, bool mxfp4, const uint8_t* xq, const float* xs,
+                           uint8_t* hq, float* hs, hipStream_t stream) {
   const int n_panels = a.I / 128;
   const int grid = 8 * ((ts.n_mt_max + 7) / 8) * n_panels;
-  hipLaunchKernelGGL(gemm_fp8_tile_kernel<true>, dim3(grid), dim3(kTileThreads), 0, stream, a.table,
-                     a.offsets, a.perm, ts.mt_expert, ts.mt_row0, ts.n_mtiles, n_panels, xq, xs, hq, hs,
-                     (uint16_t*)nullptr, a.E, a.T, a.H, a.I, a.K);
+  auto kern = mxfp4 ? gemm_fp8_tile_kernel<true, true> : gemm_fp8_tile_kernel<true, false>;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kTileThreads), 0, stream, a.table, a.offsets, a.perm, ts.mt_expert,
+                     ts.mt_row0, ts.n_mtiles, n_panels, xq, xs, hq, hs, (uint16_t*)nullptr, a.E, a.T, a.H, a.I, a.K);
 }
 
-void launch_gemm2_fp8_tile(const GemmArgs& a, const TileSched& ts, const uint8_t* hq, const float* hs, void* yp,
-                           hipStream_t stream) {
+void launch_gemm2_fp8_tile(const GemmArgs& a, const TileSched& ts, bool mxfp4, const uint8_t* hq, const float* hs,
+                           void* yp, hipStream_t stream) {
   const int n_panels = (a.H + 255) / 256;
   const int grid = 8 * ((ts.n_mt_max + 7) / 8) * n_panels;
-  hipLaunchKernelGGL(gemm_fp8_tile_kernel<false>, dim3(grid), dim3(kTileThreads), 0, stream, a.table,
-                     a.offsets, a.perm, ts.mt_expert, ts.mt_row0, ts.n_mtiles, n_panels, hq, hs, (uint8_t*)nullptr,
-                     (float*)nullptr, (uint16_t*)yp, a.E, a.T, a.H, a.I, a.K);
+  auto kern = mxfp4 ? gemm_fp8_tile_kernel<false, true> : gemm_fp8_tile_kernel<false, false>;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kTileThreads), 0, stream, a.table, a.offsets, a.perm, ts.mt_expert,
+                     ts.mt_row0, ts.n_mtiles, n_panels, hq, hs, (uint8_t*)nullptr, (float*)nullptr, (uint16_t*)yp, a.E,
+                     a.T, a.H, a.I, a.K);
 }
 
 }  // namespace dwdp

@@ -48,13 +48,15 @@ def test_pack_layout(binding):
     ctx.close()
 
 
-def _case(binding, cfg, seed, bias_kind="small"):
+def _case(binding, cfg, seed, bias_kind="small", stream_max_rows=None):
     x = inputs.make_activations(cfg, seed)
     logits = inputs.make_gate_logits(cfg, x, seed)
     bias = None if bias_kind is None else inputs.make_bias(cfg, seed, kind=bias_kind)
     w = inputs.make_expert_weights(cfg, seed)
     wd = inputs.ExpertWeights(w.w13.cuda(), w.w2.cuda(), w.s13.cuda(), w.s2.cuda())
     ctx = binding.Context(cfg)
+    if stream_max_rows is not None:
+        ctx.dwdp_set_stream_max_rows(stream_max_rows)
     wp = ctx.pack_experts(wd)
     table = binding.expert_table(wp)
     y = torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device="cuda")
@@ -70,23 +72,26 @@ def _case(binding, cfg, seed, bias_kind="small"):
     ctx.close()
 
 
+@pytest.mark.parametrize("smr", [0, 16, 1 << 30])
 @pytest.mark.parametrize("T", [1, 7, 48, 333])
-def test_layer_small_mxfp4(binding, T):
+def test_layer_small_mxfp4(binding, T, smr):
     """The scaled-down sigmoid / group-limited layer with MXFP4 weights: several 16-token passes
-    with a ragged tail, experts without tokens, shared expert."""
-    print("layer small mxfp4 T", T, flush=True)
+    with a ragged tail, experts without tokens, shared expert.  smr selects the kernels: 0 =
+    LDS-tiled for every expert, 16 = the default split, 2^30 = weight-streaming for every expert."""
+    print("layer small mxfp4 T", T, "stream_max_rows", smr, flush=True)
     cfg = dataclasses.replace(inputs.small_fp8_layer(T=T), w_dtype=inputs.W_MXFP4)
-    _case(binding, cfg, T)
+    _case(binding, cfg, T, stream_max_rows=smr)
 
 
+@pytest.mark.parametrize("smr", [0, 1 << 30])
 @pytest.mark.parametrize("H,I,T", [(1536, 1024, 37), (1408, 640, 20), (640, 384, 300), (128, 128, 5), (256, 2304, 20)])
-def test_layer_mxfp4_long_k(binding, H, I, T):
+def test_layer_mxfp4_long_k(binding, H, I, T, smr):
     """K loops of 1..18 blocks: scale groups of four K blocks with a partial last group (11, 5,
-    3, 1 blocks), odd numbers of two-block pipeline stages."""
-    print("layer mxfp4 long-k", H, I, T, flush=True)
+    3, 1 blocks), odd numbers of two-block pipeline stages, on both kernel families."""
+    print("layer mxfp4 long-k", H, I, T, smr, flush=True)
     cfg = dataclasses.replace(inputs.small_fp8_layer(T=T, H=H, I=I, E=8, K=2, n_group=1, topk_group=1),
                               w_dtype=inputs.W_MXFP4)
-    _case(binding, cfg, 21, bias_kind=None)
+    _case(binding, cfg, 21, bias_kind=None, stream_max_rows=smr)
 
 
 def test_full_size_decode_mxfp4(binding):
@@ -108,6 +113,36 @@ def test_full_size_decode_mxfp4(binding):
     roff, rperm, _ = mo.permute(rid, spec)
     np.testing.assert_array_equal(ctx.workspace("perm", (cfg.T * cfg.K,), torch.int32).cpu().numpy(), rperm)
     toks = [0, 31, 63]
+    need = sorted({int(e) for t in toks for e in rid[t]} | {cfg.E})
+    ref = mo.moe_forward(to_np(x), to_np(logits), to_np(bias), experts_numpy(w, only=need), spec, tokens=toks)
+    got = y[toks].float().cpu().numpy()
+    err, l2 = mo.error_metrics(got, ref)
+    print(f"  max-rel {err:.3e} l2-rel {l2:.3e}", flush=True)
+    assert np.isfinite(y.float().cpu().numpy()).all()
+    assert err <= tolerance(cfg), (err, l2)
+    ctx.close()
+
+
+def test_full_size_prefill_mxfp4(binding):
+    """The same layer shape at T=8192 with MXFP4 weights (every expert on the LDS-tiled kernels, in
+    the launch configuration `bench.py --workload prefill --weights mxfp4` times): routing and
+    permutation bit-exact on every token, output on sampled tokens."""
+    print("full-size prefill mxfp4: generating 257 experts on the GPU", flush=True)
+    cfg, x, logits, bias = inputs.make_layer_inputs("prefill", 1, device="cuda")
+    cfg = dataclasses.replace(cfg, w_dtype=inputs.W_MXFP4)
+    w = inputs.make_expert_weights(cfg, 1, device="cuda")
+    ctx = binding.Context(cfg)
+    wp = ctx.pack_experts(w)
+    table = binding.expert_table(wp)
+    y = torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device="cuda")
+    ctx.dwdp_moe_forward(0, x, logits, bias, table, y)
+    torch.cuda.synchronize()
+    spec = mo.spec_from(cfg)
+    rid, _ = mo.route(to_np(logits), to_np(bias), spec)
+    np.testing.assert_array_equal(ctx.workspace("topk_ids", (cfg.T, cfg.K), torch.int32).cpu().numpy(), rid)
+    roff, rperm, _ = mo.permute(rid, spec)
+    np.testing.assert_array_equal(ctx.workspace("perm", (cfg.T * cfg.K,), torch.int32).cpu().numpy(), rperm)
+    toks = [0, 4097, 8191]
     need = sorted({int(e) for t in toks for e in rid[t]} | {cfg.E})
     ref = mo.moe_forward(to_np(x), to_np(logits), to_np(bias), experts_numpy(w, only=need), spec, tokens=toks)
     got = y[toks].float().cpu().numpy()

@@ -4,8 +4,9 @@ The tile kernel loads its weight fragments with hand-issued asynchronous loads i
 registers and waits for them with explicit counters, so its correctness rests on three
 properties of the compiled code that the C++ source cannot state:
   * between the first per-block wait and the final drain, nothing but those loads writes a
-    ring register and nothing but an MFMA (as its weight operand) reads one -- a register
-    copied or reused while a load is still in flight would hold stale or clobbered data;
+    ring register and nothing but an MFMA (as its weight operand; with MXFP4 weights also the
+    shift that extracts a block's scale byte) reads one -- a register copied or reused while a
+    load is still in flight would hold stale or clobbered data;
   * the only vector-memory waits inside that region are the two the source writes
     (vmcnt(9) or vmcnt(10) per K block, vmcnt(0) at the drain) -- an extra compiler-inserted wait means it
     modelled one of the hand-issued operations and the counting no longer holds;
@@ -22,7 +23,16 @@ import pytest
 from paper_2604_01621_amd import build as dwdp_build
 
 SRC = os.path.join(dwdp_build.CSRC, "gemm_tile.hip")
-RING_LOAD = re.compile(r"\s*global_load_dwordx4 v\[(\d+):(\d+)\], v(\d+), s\[\d+:\d+\](?: offset:\d+)? nt")
+# weight loads into the ring: 16 bytes per lane (FP8 codes, MXFP4 codes) or, for the MXFP4 scale
+# dwords, 4 bytes per lane into a single register
+RING_LOAD = re.compile(r"\s*global_load_dword(?:x4 v\[(\d+):(\d+)\]| v(\d+)), v(\d+), s\[\d+:\d+\](?: offset:\d+)?(?: nt)?$")
+
+
+def _ring_regs(m):
+    """Destination registers and address register of a ring load."""
+    if m.group(1) is not None:
+        return set(range(int(m.group(1)), int(m.group(2)) + 1)), int(m.group(4))
+    return {int(m.group(3))}, int(m.group(4))
 
 
 def _regs(text):
@@ -46,12 +56,18 @@ def tile_asm(tmp_path_factory):
 
 def _kernels(asm):
     parts = re.split(r"\n(?=_ZN4dwdp20gemm_fp8_tile_kernel\w+:)", asm)[1:]
-    assert len(parts) == 2, "expected the GEMM-1 and GEMM-2 instantiations"
+    assert len(parts) == 4, "expected GEMM-1 and GEMM-2, each for FP8 and MXFP4 weights"
     for k in parts:
         body = k.split(".end_amdhsa_kernel")[0]
         meta = k[len(body):]
         lines = [l for l in body.split("\n") if l.strip() and not l.strip().startswith((";", ".", "//"))]
-        yield k.split(":")[0], lines, k
+        name = k.split(":")[0]
+        yield name, lines, k
+
+
+def _is_mx(name):
+    # template arguments <G1, MX> are mangled as ILb<G1>ELb<MX>E
+    return re.search(r"ILb[01]ELb1E", name) is not None
 
 
 def test_ring_registers_are_left_alone(tile_asm):
@@ -61,9 +77,9 @@ def test_ring_registers_are_left_alone(tile_asm):
         assert len(loads) == 20, (name, len(loads))
         ring = set()
         for i in loads:
-            m = RING_LOAD.match(lines[i])
-            ring.update(range(int(m.group(1)), int(m.group(2)) + 1))
-        assert len(ring) == 48, (name, sorted(ring))   # 3 fragments x 16 registers
+            ring |= _ring_regs(RING_LOAD.match(lines[i]))[0]
+        # 3 fragments: FP8 16 registers of codes; MXFP4 8 of codes and 2 scale dwords
+        assert len(ring) == (30 if _is_mx(name) else 48), (name, sorted(ring))
         first = next(i for i, l in enumerate(lines) if "vmcnt(9)" in l)
         drain = next(i for i, l in enumerate(lines) if "vmcnt(0)" in l and i > loads[-1])
         bad = []
@@ -71,11 +87,16 @@ def test_ring_registers_are_left_alone(tile_asm):
             t = l.strip()
             m = RING_LOAD.match(l)
             if m:
-                if int(m.group(3)) in ring:
+                if _ring_regs(m)[1] in ring:
                     bad.append(t)       # an address offset held in a ring register
                 continue
             if not (_regs(t) & ring):
                 continue
+            if t.startswith("v_lshrrev_b32") and _is_mx(name):
+                # MXFP4: this block's scale byte is shifted out of its (landed) scale dword into
+                # another register; a read after the wait, like the MFMA's
+                if int(re.match(r"v_lshrrev_b32_e32 v(\d+),", t).group(1)) not in ring:
+                    continue
             if t.startswith("v_mfma"):
                 ops = re.findall(r"v\[(\d+):(\d+)\]", t)
                 dst = set(range(int(ops[0][0]), int(ops[0][1]) + 1))
