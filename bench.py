@@ -46,6 +46,9 @@ def parse():
     ap.add_argument("--weights", default="fp8", choices=["fp8", "mxfp4"],
                     help="expert weight format of the decode/prefill/skew workloads: block-scaled FP8 (the "
                          "headline configuration) or MXFP4 (FP4 codes with a power-of-two scale per 32)")
+    ap.add_argument("--window-pad-ms", type=float, default=0.0,
+                    help="pipeline workload: extra compute per layer (a spin kernel on the compute stream) standing "
+                         "in for the attention that shares the paper's compute window")
     ap.add_argument("--merge-baseline", action="store_true",
                     help="pipeline workload: merge resident and staged experts into one contiguous image before "
                          "every layer (the naive split-weight baseline) instead of reading them in place")

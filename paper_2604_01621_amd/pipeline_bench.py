@@ -67,7 +67,25 @@ def run(args):
         merged_dev = ctx.dwdp_merge_experts(0, tables_host[0], m_w13, m_s13, m_w2, m_s2).to(dev)   # same for all layers
         torch.cuda.synchronize()
 
+    # Stand-in for the rest of the compute window of a layer (the paper's window also holds the next
+    # layer's attention, Section 3): a spin kernel of one wavefront on the compute stream, no memory traffic.
+    pad_ms = float(getattr(args, "window_pad_ms", 0.0) or 0.0)
+    pad_cycles = 0
+    if pad_ms > 0:
+        with torch.cuda.stream(stream):
+            probe = 20_000_000
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda._sleep(probe)                      # warm
+            e0.record(stream)
+            torch.cuda._sleep(probe)
+            e1.record(stream)
+        torch.cuda.synchronize()
+        pad_cycles = int(probe * pad_ms / e0.elapsed_time(e1))
+
     def forward(l):
+        if pad_cycles:
+            with torch.cuda.stream(stream):
+                torch.cuda._sleep(pad_cycles)
         if merge:
             ctx.dwdp_merge_experts(l, tables_host[l], m_w13, m_s13, m_w2, m_s2)
             ctx.dwdp_moe_forward(l, xs[l], lgs[l], bs[l], merged_dev, ys[l])
@@ -137,6 +155,8 @@ def run(args):
                    else "read in place through the expert-pointer table",
                    "prefetch_bytes_per_layer": pf_bytes},
         "ms_per_layer": ms_per_layer, "compute_alone_ms_per_layer": compute_alone_ms,
+        "window_pad_ms": pad_ms,
+        "exposed_copy_ms_per_layer": max(ms_per_layer - compute_alone_ms, 0.0),
         "copy_alone_ms_per_layer": copy_alone_ms, "copy_alone_gbs": pf_bytes / (copy_alone_ms * 1e-3) / 1e9,
         "overlap": {"copy_time_overlapped_with_gemm_frac": frac,
                     "avg_copy_ms": copy_ms_total / max(n_copies, 1), "copies": n_copies,
