@@ -144,7 +144,11 @@ class Context:
             lib.dwdp_destroy(self.h)
             self.h = None
 
-    __del__ = close
+    def __del__(self):
+        # at interpreter shutdown the module globals may already be gone; the process is ending
+        # and the driver reclaims the context's device memory
+        if lib is not None:
+            self.close()
 
     def _check(self, st: int):
         if st != OK:
