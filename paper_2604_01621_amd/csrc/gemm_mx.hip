@@ -105,15 +105,22 @@ __device__ __forceinline__ void mx_mainloop(const uint8_t* const (&wt)[NT], cons
   MxStage<NT> f0, f1;
   mx_load_scales<NT>(f0, st, 0);
   mx_load<NT>(f0, wt, xrow, xsrow, 0, nkb);
-  for (int s = 0; s < nst; s += 2) {
+  int s = 0;
+  for (; s + 2 < nst; s += 2) {
 #pragma unroll
     for (int j = 0; j < NT; j++) f1.sc[j] = f0.sc[j];  // same group
     mx_load<NT>(f1, wt, xrow, xsrow, s + 1, nkb);
     mx_mma<NT, 0>(f0, acc, s, nkb);
-    mx_load_scales<NT>(f0, st, min(s / 2 + 1, ng - 1));
-    mx_load<NT>(f0, wt, xrow, xsrow, min(s + 2, nst - 1), nkb);
+    mx_load_scales<NT>(f0, st, s / 2 + 1);
+    mx_load<NT>(f0, wt, xrow, xsrow, s + 2, nkb);
     mx_mma<NT, 1>(f1, acc, s + 1, nkb);
   }
+  // last group: nothing left to load for f0 (a clamped re-read would still take request slots)
+#pragma unroll
+  for (int j = 0; j < NT; j++) f1.sc[j] = f0.sc[j];
+  mx_load<NT>(f1, wt, xrow, xsrow, s + 1, nkb);
+  mx_mma<NT, 0>(f0, acc, s, nkb);
+  mx_mma<NT, 1>(f1, acc, s + 1, nkb);
 }
 
 // GEMM-1: task = (expert slot e, block jb of 128 h columns); wave w owns gate tiles 2w, 2w+1 and

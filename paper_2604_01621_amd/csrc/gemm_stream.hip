@@ -78,7 +78,8 @@ __device__ __forceinline__ void mma_frag(const Frag<NT, SG>& f, v4f (&acc)[NT]) 
 }
 
 // Branch-free steady state (so the compiler can count outstanding loads and let the next
-// batch stay in flight behind the MFMAs), plain loop for a tail of nkb % (2*kU) blocks.
+// batch stay in flight behind the MFMAs), a last round without loads for the batch after it,
+// plain loop for a tail of nkb % (2*kU) blocks.
 template <int NT, int SG>
 __device__ __forceinline__ void stream_mainloop(const uint8_t* const (&wt)[NT], const float* const (&swp)[SG],
                                                 const uint8_t* xrow, const float* xsrow, int nkb, v4f (&acc)[NT]) {
@@ -88,17 +89,24 @@ __device__ __forceinline__ void stream_mainloop(const uint8_t* const (&wt)[NT], 
     Frag<NT, SG> f0[kU], f1[kU];
 #pragma unroll
     for (int u = 0; u < kU; u++) load_frag<NT, SG>(f0[u], wt, swp, xrow, xsrow, u);
-    for (int kb0 = 0; kb0 < nmain; kb0 += kStep) {
+    int kb0 = 0;
+    for (; kb0 + kStep < nmain; kb0 += kStep) {
 #pragma unroll
       for (int u = 0; u < kU; u++) load_frag<NT, SG>(f1[u], wt, swp, xrow, xsrow, kb0 + kU + u);
 #pragma unroll
       for (int u = 0; u < kU; u++) mma_frag<NT, SG>(f0[u], acc);
-      // the last round re-reads block nkb-1 instead of running past the end; it is not used
 #pragma unroll
-      for (int u = 0; u < kU; u++) load_frag<NT, SG>(f0[u], wt, swp, xrow, xsrow, min(kb0 + kStep + u, nkb - 1));
+      for (int u = 0; u < kU; u++) load_frag<NT, SG>(f0[u], wt, swp, xrow, xsrow, kb0 + kStep + u);
 #pragma unroll
       for (int u = 0; u < kU; u++) mma_frag<NT, SG>(f1[u], acc);
     }
+    // last round: nothing left to load for f0 (a clamped re-read would still take request slots)
+#pragma unroll
+    for (int u = 0; u < kU; u++) load_frag<NT, SG>(f1[u], wt, swp, xrow, xsrow, kb0 + kU + u);
+#pragma unroll
+    for (int u = 0; u < kU; u++) mma_frag<NT, SG>(f0[u], acc);
+#pragma unroll
+    for (int u = 0; u < kU; u++) mma_frag<NT, SG>(f1[u], acc);
   }
   for (int kb = nmain; kb < nkb; kb++) {
     Frag<NT, SG> f;
@@ -296,21 +304,27 @@ __global__ __launch_bounds__(kStreamThreads, 2) void gemm2_fp8_stream_kernel(
           G2Frag f0[kU2], f1[kU2];
 #pragma unroll
           for (int u = 0; u < kU2; u++) g2_load(f0[u], wt, lane16, swp, xb0, xb1, xsa, u, kc + u);
-          for (int kb0 = 0; kb0 < nmain; kb0 += kStep) {
+          int kb0 = 0;
+          for (; kb0 + kStep < nmain; kb0 += kStep) {
 #pragma unroll
             for (int u = 0; u < kU2; u++)
               g2_load(f1[u], wt, lane16, swp, xb0, xb1, xsa, kb0 + kU2 + u, kc + kb0 + kU2 + u);
 #pragma unroll
             for (int u = 0; u < kU2; u++) g2_mma(f0[u], acc);
-            // the last round re-reads the chunk's last block instead of running past it; unused
 #pragma unroll
-            for (int u = 0; u < kU2; u++) {
-              const int kn = min(kb0 + kStep + u, nkc - 1);
-              g2_load(f0[u], wt, lane16, swp, xb0, xb1, xsa, kn, kc + kn);
-            }
+            for (int u = 0; u < kU2; u++)
+              g2_load(f0[u], wt, lane16, swp, xb0, xb1, xsa, kb0 + kStep + u, kc + kb0 + kStep + u);
 #pragma unroll
             for (int u = 0; u < kU2; u++) g2_mma(f1[u], acc);
           }
+          // last round of the chunk: nothing left to load for f0
+#pragma unroll
+          for (int u = 0; u < kU2; u++)
+            g2_load(f1[u], wt, lane16, swp, xb0, xb1, xsa, kb0 + kU2 + u, kc + kb0 + kU2 + u);
+#pragma unroll
+          for (int u = 0; u < kU2; u++) g2_mma(f0[u], acc);
+#pragma unroll
+          for (int u = 0; u < kU2; u++) g2_mma(f1[u], acc);
         }
         for (int kb = nmain; kb < nkc; kb++) {
           G2Frag f;
