@@ -49,6 +49,9 @@ def parse():
     ap.add_argument("--window-pad-ms", type=float, default=0.0,
                     help="pipeline workload: extra compute per layer (a spin kernel on the compute stream) standing "
                          "in for the attention that shares the paper's compute window")
+    ap.add_argument("--pullers", type=int, default=1,
+                    help="pipeline workload: with N > 1, time N contexts (stand-ins for N ranks) that pull the "
+                         "same layer from the same source pool at once, over slice sizes and both copy engines")
     ap.add_argument("--merge-baseline", action="store_true",
                     help="pipeline workload: merge resident and staged experts into one contiguous image before "
                          "every layer (the naive split-weight baseline) instead of reading them in place")
@@ -101,7 +104,7 @@ def main():
 
     if args.workload == "pipeline":
         from paper_2604_01621_amd import pipeline_bench
-        out = pipeline_bench.run(args)
+        out = pipeline_bench.run_pullers(args) if args.pullers > 1 else pipeline_bench.run(args)
         print(json.dumps(out))
         return
 

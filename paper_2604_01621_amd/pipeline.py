@@ -87,17 +87,37 @@ class SplitWeightLayers:
         """Free the row-major copies kept for the oracle (large workloads)."""
         self.logical = [None] * self.n_layers
 
-    def _table(self, l: int, device) -> torch.Tensor:
+    def _table(self, l: int, device, staging=None) -> torch.Tensor:
         cfg = self.cfg
+        staging = self.staging[l % 2] if staging is None else staging
         rows = []
         for e in range(cfg.E):
             if e < self.n_resident:
                 rows.append(self.resident[l].row(e))
             else:
                 p = (e - self.n_resident) // self.per
-                rows.append(self.staging[l % 2][p].row(e - self.ranges[p][0]))
+                rows.append(staging[p].row(e - self.ranges[p][0]))
         rows.append(self.resident[l].row(self.n_resident))      # shared expert
         return torch.tensor(rows, dtype=torch.int64).to(device)
+
+    def new_puller_staging(self, device="cuda") -> List[_Shard]:
+        """One more staging buffer over the same peers: the landing area of another puller (a
+        second context standing for another rank that pulls from the same sources)."""
+        return [_Shard(self.cfg, self.per, device) for _ in range(self.n_peers)]
+
+    def puller_table(self, l: int, staging, device="cuda") -> torch.Tensor:
+        """Layer l's table for a puller that stages into `staging` (from new_puller_staging)."""
+        return self._table(l, device, staging)
+
+    def puller_prefetch(self, ctx, l: int, staging, slice_bytes: int, first_peer: int = 0):
+        """dwdp_prefetch_layer(l) of context `ctx` into `staging`, peers visited in the order
+        first_peer, first_peer + 1, ... (paper Section 4.3.2: every puller walks its own peer order)."""
+        src, dst = [], []
+        for i in range(self.n_peers):
+            p = (first_peer + i) % self.n_peers
+            src += self.peer[l][p].ptrs()
+            dst += staging[p].ptrs()
+        ctx.dwdp_prefetch_layer(l, src, dst, self.peer[l][0].nbytes(), self.n_peers, N_PARAMS, slice_bytes)
 
     def all_resident_table(self, l: int, device="cuda") -> torch.Tensor:
         """Table of the same layer reading the peer pool in place (reference for equivalence tests)."""
@@ -126,9 +146,10 @@ class SplitWeightLayers:
         src, dst, nb = self.prefetch_args(l)
         ctx.dwdp_prefetch_layer(l, src, dst, nb, self.n_peers, N_PARAMS, slice_bytes)
 
-    def poison_staging(self, b: int):
-        """Fill staging buffer b with 0xFF bytes (e4m3 NaN codes, NaN scales) on the current stream."""
-        for sh in self.staging[b]:
+    def poison_staging(self, b: int, staging=None):
+        """Fill staging buffer b (or the given puller's landing buffer) with 0xFF bytes (e4m3 NaN
+        codes, NaN scales) on the current stream."""
+        for sh in (self.staging[b] if staging is None else staging):
             sh.w13.fill_(0xFF)
             sh.w2.fill_(0xFF)
             sh.s13.view(torch.uint8).fill_(0xFF)

@@ -2,6 +2,8 @@
 64 resident + 192 staged experts per layer).  Called by bench.py --workload pipeline."""
 from __future__ import annotations
 
+import sys
+import threading
 import time
 
 import torch
@@ -168,4 +170,83 @@ def run(args):
         "hbm_traffic_gbs": (active * eb + 2 * pf_bytes) / (ms_per_layer * 1e-3) / 1e9,
     }
     ctx.close()
+    return out
+
+
+def run_pullers(args):
+    """Several pullers on one source (paper Section 4.3: many-to-one contention and the sliced,
+    peer-interleaved copy order of Section 4.3.2), emulated on one GPU: every puller is a context of
+    its own (own copy stream, own landing buffer, issued from a host thread of its own) and all
+    of them fetch the same layer's non-resident experts from the same pool at the same time.
+    Reports, per copy engine, slice size and peer order, when each puller's copies were done."""
+    dev = torch.device("cuda:0")
+    cfg = inputs.WORKLOADS["pipeline"]
+    n_res, n_peers, P = 64, 3, args.pullers
+    ctxs = [binding.Context(cfg, n_layers=1, stream=torch.cuda.Stream()) for _ in range(P)]
+    layers = pipeline.SplitWeightLayers(ctxs[0], cfg, 1, n_res, n_peers, seed=args.seed, device=dev)
+    layers.drop_logical()
+    torch.cuda.empty_cache()
+    stagings = [layers.staging[0]] + [layers.new_puller_staging(dev) for _ in range(P - 1)]
+    tables = [layers.puller_table(0, st, dev) for st in stagings]
+    copy_streams = [torch.cuda.ExternalStream(c.copy_stream_handle()) for c in ctxs]
+    x0 = torch.empty(0, cfg.H, dtype=torch.bfloat16, device=dev)
+    lg0 = torch.empty(0, cfg.E, dtype=torch.float32, device=dev)
+    b0 = inputs.make_bias(cfg, args.seed, device=dev, kind="zero")
+    pf_bytes = layers.prefetch_bytes()
+    reps = max(2, min(args.steps, 5))
+
+    def one_round(engine, slice_bytes, rotated, active):
+        for c in ctxs:
+            c.dwdp_set_copy_engine(engine, getattr(args, "copy_wgs", 512))
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(active)]
+        gate = threading.Barrier(active)
+        errs = []
+
+        def pull(p):
+            try:
+                gate.wait()
+                layers.puller_prefetch(ctxs[p], 0, stagings[p], slice_bytes, first_peer=(p % n_peers) if rotated else 0)
+                evs[p].record(copy_streams[p])
+            except Exception as ex:      # surfaced after the join
+                errs.append(ex)
+
+        e0.record(torch.cuda.current_stream())
+        th = [threading.Thread(target=pull, args=(p,)) for p in range(active)]
+        for t in th:
+            t.start()
+        for t in th:
+            t.join()
+        if errs:
+            raise errs[0]
+        for p in range(active):     # T = 0 layer: takes the buffer and releases it for the next round
+            ctxs[p].dwdp_moe_forward(0, x0, lg0, b0, tables[p], x0)
+        torch.cuda.synchronize()
+        return [e0.elapsed_time(ev) for ev in evs]
+
+    rows = []
+    for engine in (1, 0):
+        for slice_mib in (1, 16, 256):
+            for active, rotated in ((1, False), (P, False), (P, True)):
+                one_round(engine, slice_mib << 20, rotated, active)     # warm: plans cached, pages touched
+                t = [one_round(engine, slice_mib << 20, rotated, active) for _ in range(reps)]
+                done = [sum(r[p] for r in t) / reps for p in range(active)]
+                rows.append({"copy_engine": "copy-plan kernel" if engine == 1 else "hipMemcpyAsync per slice",
+                             "slice_mib": slice_mib, "pullers": active,
+                             "peer_order": "rotated per puller" if rotated else "same for all",
+                             "done_ms": [round(v, 3) for v in done],
+                             "last_done_ms": round(max(done), 3),
+                             "spread": round((max(done) - min(done)) / max(done), 3),
+                             "aggregate_gbs": round(active * pf_bytes / (max(done) * 1e-3) / 1e9, 1)})
+                print(rows[-1], flush=True, file=sys.stderr)
+    ref = next(r for r in rows if r["copy_engine"] == "copy-plan kernel" and r["slice_mib"] == 1
+               and r["pullers"] == P and r["peer_order"] == "rotated per puller")
+    out = {"metric": "multi_puller_prefetch_last_done_ms", "value": ref["last_done_ms"], "unit": "ms", "n_gpus": 1,
+           "steps": reps, "warmup": 1, "ms_per_step": ref["last_done_ms"], "higher_is_better": False,
+           "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+           "config": {"workload": "pipeline layer 0: %d pullers x 192 staged experts from one 3-peer pool" % P,
+                      "prefetch_bytes_per_puller": pf_bytes}, "rows": rows}
+    for c in ctxs:
+        c.close()
     return out

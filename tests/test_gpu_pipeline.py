@@ -105,6 +105,38 @@ def test_pipeline_layers_match_oracle(env):
         assert err <= tolerance(cfg)
 
 
+@pytest.mark.parametrize("engine", [0, 1])
+def test_two_pullers_share_one_source(env, engine):
+    """Two contexts (the pullers of two ranks, paper Section 4.3) fetch the same layer from the
+    same peers at the same time, each in its own peer order and into its own landing buffer:
+    both layers equal the in-place reference bit for bit."""
+    binding, pipeline, cfg, ctx, layers, xs, lgs, bs = env
+    print("two pullers, engine", engine, flush=True)
+    l = 1
+    ref = _reference_outputs(ctx, cfg, layers, xs, lgs, bs)[l].float().cpu().numpy()
+    ctx2 = binding.Context(cfg, n_layers=N_LAYERS)
+    try:
+        st2 = layers.new_puller_staging()
+        table2 = layers.puller_table(l, st2)
+        for c in (ctx, ctx2):
+            c.dwdp_set_copy_engine(engine, 24)
+        layers.poison_staging(l % 2)
+        layers.poison_staging(l % 2, st2)
+        torch.cuda.synchronize()
+        layers.puller_prefetch(ctx, l, layers.staging[l % 2], 4096, first_peer=0)
+        layers.puller_prefetch(ctx2, l, st2, 4096, first_peer=1)
+        y1 = torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device="cuda")
+        y2 = torch.empty_like(y1)
+        ctx.dwdp_moe_forward(l, xs[l], lgs[l], bs[l], layers.tables[l], y1)
+        ctx2.dwdp_moe_forward(l, xs[l], lgs[l], bs[l], table2, y2)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(y1.float().cpu().numpy(), ref)
+        np.testing.assert_array_equal(y2.float().cpu().numpy(), ref)
+    finally:
+        ctx2.close()
+        ctx.dwdp_set_copy_engine(0)
+
+
 def test_prefetch_protocol_errors(env):
     binding, pipeline, cfg, ctx, layers, xs, lgs, bs = env
     print("pipeline protocol", flush=True)
