@@ -221,6 +221,20 @@ def test_layer_fp8_tile_boundaries(binding, T):
     _layer_case(binding, cfg, x, logits, None, w, check_intermediates=True, stream_max_rows=0)
 
 
+@pytest.mark.parametrize("T", [200, 500])
+def test_layer_maximum_expert_and_topk_counts(binding, T):
+    """The largest routing set-up the library accepts (1024 experts, top-32, 8 groups of 128) on a
+    narrow layer: routing ids, permutation and output, with the permutation on one workgroup
+    (T = 200) and on several (T = 500)."""
+    print("layer E=1024 K=32 T", T, flush=True)
+    cfg = inputs.small_fp8_layer(T=T, H=128, I=128, E=1024, K=32, n_group=8, topk_group=4)
+    x = inputs.make_activations(cfg, 300 + T)
+    logits = inputs.make_gate_logits(cfg, x, 300 + T)
+    bias = inputs.make_bias(cfg, 300 + T, kind="small")
+    w = inputs.make_expert_weights(cfg, 300 + T)
+    _layer_case(binding, cfg, x, logits, bias, w, check_intermediates=True)
+
+
 def test_layer_small_fp8_no_shared_and_empty(binding):
     print("layer small fp8 no shared / T=0", flush=True)
     cfg = inputs.small_fp8_layer(T=40, has_shared=0, E=32, n_group=4, topk_group=2, K=4, H=384, I=128)
