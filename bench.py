@@ -23,7 +23,7 @@ FP8_PEAK_TFLOPS = 5000.0     # MI355X dense FP8 MFMA, published
 # FETCH_SIZE x 2.0 + WRITE_SIZE, calibrated against a 1 GiB copy), keyed by (workload, seed, T); None
 # when this configuration was not profiled.
 PROFILED_TRAFFIC = {("decode", 1, 64): (2325711 * 2 + 1238) * 1024,
-                    ("prefill", 1, 8192): (4518404 * 2 + 152102) * 1024}
+                    ("prefill", 1, 8192): (4361665 * 2 + 152102) * 1024}
 
 
 def parse():

@@ -44,7 +44,11 @@
 //
 // Workgroups are numbered so that all weight panels of one M tile run on the same XCD back
 // to back and share the token rows in its L2: block b runs on XCD b % 8 and handles M tile
-// (b/8 / n_panels) * 8 + b % 8, panel (b/8) % n_panels.
+// (b/8 / n_panels) * 8 + b % 8, panel (b/8) % n_panels.  With many M tiles (kPairMinTiles or
+// more) an XCD takes them in pairs of list neighbours, panel by panel -- (pair, panel 0, first),
+// (pair, panel 0, second), (pair, panel 1, first) ... -- the same 2 x 16 workgroups at a time,
+// but the further M tiles of an expert with many rows (neighbours in the list) then fetch a
+// weight panel while the XCD's L2 still holds it.
 //
 // GEMM-1 (G1): wave w owns gate rows and up rows of 16 h columns of the panel (the 32 rows of
 // its A operand), epilogue silu(g)*u, per-token amax over the panel's 128 h columns (LDS, 8
@@ -71,6 +75,7 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kBM = kTileM;     // tokens per workgroup tile (288)
 constexpr int kTT = kBM / 32;   // 32-token tiles per workgroup (9)
+constexpr int kPairMinTiles = 32;  // M tiles from which an XCD takes them in pairs (4 per XCD)
 constexpr int kTileWaves = 8;
 constexpr int kTileThreads = 64 * kTileWaves;
 constexpr int kLdsB = kBM * 128;         // one token image: 36 KiB
@@ -166,10 +171,20 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   }
   const int xcd = blockIdx.x & 7;
   const int s = blockIdx.x >> 3;
-  const int mq = s / n_panels;
-  const int panel = s - mq * n_panels;
-  const int m = mq * 8 + xcd;
-  if (m >= *n_mtiles) return;
+  const int n_mt = *n_mtiles;
+  int m, panel;
+  if (n_mt >= kPairMinTiles) {
+    // two consecutive M tiles side by side on one XCD
+    const int pq = s / (2 * n_panels);
+    const int within = s - pq * (2 * n_panels);
+    panel = within >> 1;
+    m = (pq * 8 + xcd) * 2 + (within & 1);
+  } else {
+    const int mq = s / n_panels;
+    panel = s - mq * n_panels;
+    m = mq * 8 + xcd;
+  }
+  if (m >= n_mt) return;
   // wave-uniform values go through readfirstlane so that everything derived from them
   // (weight/scale pointers, tile counts) lives in scalar registers and is loaded with s_load
   const int e = __builtin_amdgcn_readfirstlane(mt_expert[m]);
@@ -587,10 +602,13 @@ int tile_mtiles_cap(int rows, int n_slots, int stream_max_rows) {
   return rows / kBM + (int)(by_rows < n_slots ? by_rows : n_slots) + 1;
 }
 
+// covers both numberings of the kernel: M tiles rounded up to whole pairs on all 8 XCDs
+static int tile_grid(int n_mt_max, int n_panels) { return 16 * ((n_mt_max + 15) / 16) * n_panels; }
+
 void launch_gemm1_fp8_tile(const GemmArgs& a, const TileSched& ts, bool mxfp4, const uint8_t* xq, const float* xs,
                            uint8_t* hq, float* hs, hipStream_t stream) {
   const int n_panels = a.I / 128;
-  const int grid = 8 * ((ts.n_mt_max + 7) / 8) * n_panels;
+  const int grid = tile_grid(ts.n_mt_max, n_panels);
   auto kern = mxfp4 ? gemm_fp8_tile_kernel<true, true> : gemm_fp8_tile_kernel<true, false>;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kTileThreads), 0, stream, a.table, a.offsets, a.perm, ts.mt_expert,
                      ts.mt_row0, ts.n_mtiles, n_panels, xq, xs, hq, hs, (uint16_t*)nullptr, a.E, a.T, a.H, a.I, a.K);
@@ -599,7 +617,7 @@ void launch_gemm1_fp8_tile(const GemmArgs& a, const TileSched& ts, bool mxfp4, c
 void launch_gemm2_fp8_tile(const GemmArgs& a, const TileSched& ts, bool mxfp4, const uint8_t* hq, const float* hs,
                            void* yp, hipStream_t stream) {
   const int n_panels = (a.H + 255) / 256;
-  const int grid = 8 * ((ts.n_mt_max + 7) / 8) * n_panels;
+  const int grid = tile_grid(ts.n_mt_max, n_panels);
   auto kern = mxfp4 ? gemm_fp8_tile_kernel<false, true> : gemm_fp8_tile_kernel<false, false>;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kTileThreads), 0, stream, a.table, a.offsets, a.perm, ts.mt_expert,
                      ts.mt_row0, ts.n_mtiles, n_panels, hq, hs, (uint8_t*)nullptr, (float*)nullptr, (uint16_t*)yp, a.E,

@@ -221,6 +221,17 @@ def test_layer_fp8_tile_boundaries(binding, T):
     _layer_case(binding, cfg, x, logits, None, w, check_intermediates=True, stream_max_rows=0)
 
 
+def test_layer_fp8_many_mtiles(binding):
+    """Enough 288-row M tiles (35: 11 of the shared expert, about 3 per routed expert) for the tiled
+    kernels' paired numbering of M tiles, which small layers do not reach."""
+    print("layer fp8 many M tiles", flush=True)
+    cfg = inputs.small_fp8_layer(T=3000, H=256, I=128, E=8, K=2, n_group=1, topk_group=1)
+    x = inputs.make_activations(cfg, 77)
+    logits = inputs.make_gate_logits(cfg, x, 77)
+    w = inputs.make_expert_weights(cfg, 77)
+    _layer_case(binding, cfg, x, logits, None, w, check_intermediates=True, stream_max_rows=0)
+
+
 @pytest.mark.parametrize("T", [200, 500])
 def test_layer_maximum_expert_and_topk_counts(binding, T):
     """The largest routing set-up the library accepts (1024 experts, top-32, 8 groups of 128) on a
