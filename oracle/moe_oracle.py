@@ -18,7 +18,10 @@ oracle takes each expert's weights by value.
 
 Parity pins (tests/test_oracle_*.py): brute-force per-token selection, closed
 forms for the e4m3 codec, library softmax / matmul special cases, permutation
-invariants, dense-sum identity for combine.  The absolute MoE output values have
+invariants, dense-sum identity for combine (FP8 and MXFP4 weights), hand-valued
+cases for the error metrics and the selection-margin report, a library-matmul
+evaluation of the report-only reference without activation quantisation.
+The absolute MoE output values have
 no printed worked example in the paper: "parity unpinned" by the paper for
 moe_forward's numeric output, pinned only by the identities above.
 """
@@ -289,18 +292,24 @@ def silu(g: np.ndarray) -> np.ndarray:
     return g / (1.0 + np.exp(-g))
 
 
-def expert_mlp(x_rows: np.ndarray, expert: ExpertNumpy, spec: LayerSpec) -> np.ndarray:
+def expert_mlp(x_rows: np.ndarray, expert: ExpertNumpy, spec: LayerSpec, act_quant: bool = True) -> np.ndarray:
     """o = W_down ( QDQ( silu(W_gate x~) * (W_up x~) ) ),  x~ = QDQ(x), rows of x_rows at once.
 
     QDQ is the per-token, per-128 e4m3 activation quantisation and exists for FP8 and MXFP4
     weights (the matrix cores need an FP8 activation operand beside them, so the quantisation
     is part of the function both sides compute); for bf16 weights it is the identity.  fp64
     everywhere else.
+
+    act_quant=False drops both QDQ steps: the same dequantised weights applied to the
+    un-quantised activations.  That is the other reading of "bf16 activations, FP8 weights"
+    (a weight-only-quantised layer); it is never the parity reference, tests and the
+    benchmark only REPORT the distance of the GPU result to it, so that the cost of
+    quantising the activations stays visible.
     """
     I = spec.I
     w13, w2 = expert.dense()
     xr = np.asarray(x_rows, dtype=np.float64)
-    quantised = spec.w_dtype in (W_FP8, W_MXFP4)
+    quantised = act_quant and spec.w_dtype in (W_FP8, W_MXFP4)
     if quantised:
         xr = qdq_act(xr)[0]
     gu = xr @ w13.T
@@ -312,12 +321,13 @@ def expert_mlp(x_rows: np.ndarray, expert: ExpertNumpy, spec: LayerSpec) -> np.n
 
 def moe_forward(x: np.ndarray, logits: np.ndarray, bias: Optional[np.ndarray],
                 experts: Sequence[Optional[ExpertNumpy]], spec: LayerSpec,
-                tokens: Optional[Sequence[int]] = None) -> np.ndarray:
+                tokens: Optional[Sequence[int]] = None, act_quant: bool = True) -> np.ndarray:
     """y_t = sum_k w_{t,k} * MLP_{e_{t,k}}(x_t)  (+ MLP_shared(x_t), weight 1, not scaled).
 
     experts[e] for e < E are routed experts, experts[E] the shared one.  Works expert by
     expert over the permuted rows (one dequantised expert in memory at a time).  `tokens`
     restricts the output to a subset of tokens (experts none of them selects may be None).
+    act_quant: see expert_mlp (False = report-only reference without activation quantisation).
     Returns fp64 [len(tokens) or T, H].
     """
     T = x.shape[0]
@@ -334,11 +344,11 @@ def moe_forward(x: np.ndarray, logits: np.ndarray, bias: Optional[np.ndarray],
             continue
         ts = np.array([f // spec.K for f in rows])
         ks = np.array([f % spec.K for f in rows])
-        o = expert_mlp(xf[ts], experts[e], spec)
+        o = expert_mlp(xf[ts], experts[e], spec, act_quant)
         for i in range(len(rows)):
             y[pos[int(ts[i])]] += float(w[ts[i], ks[i]]) * o[i]
     if spec.has_shared:
-        o = expert_mlp(xf[tok], experts[spec.E], spec)
+        o = expert_mlp(xf[tok], experts[spec.E], spec, act_quant)
         y += o
     return y
 
@@ -350,9 +360,10 @@ def moe_forward_bruteforce(x, logits, bias, experts, spec: LayerSpec) -> np.ndar
     ids, w = route(logits, bias, spec)
     y = np.zeros((T, spec.H), dtype=np.float64)
     dense = [ex.dense() if ex is not None else None for ex in experts]
+    quantised = spec.w_dtype in (W_FP8, W_MXFP4)     # FP8 activations beside FP8 and MXFP4 weights
     for t in range(T):
         xt = np.asarray(x[t], dtype=np.float64)[None, :]
-        if spec.w_dtype == W_FP8:
+        if quantised:
             xt = qdq_act(xt)[0]
         chosen = [(int(ids[t, k]), float(w[t, k])) for k in range(spec.K)]
         if spec.has_shared:
@@ -362,7 +373,7 @@ def moe_forward_bruteforce(x, logits, bias, experts, spec: LayerSpec) -> np.ndar
             g = w13[:spec.I] @ xt[0]
             u = w13[spec.I:] @ xt[0]
             h = (g / (1.0 + np.exp(-g)) * u)[None, :]
-            if spec.w_dtype == W_FP8:
+            if quantised:
                 h = qdq_act(h)[0]
             y[t] += wk * (w2 @ h[0])
     return y
@@ -374,3 +385,62 @@ def error_metrics(y: np.ndarray, ref: np.ndarray) -> Tuple[float, float]:
     ref = np.asarray(ref, dtype=np.float64)
     d = np.abs(y - ref)
     return float(d.max() / np.abs(ref).max()), float(np.linalg.norm(y - ref) / np.linalg.norm(ref))
+
+
+def error_metric_rows(y: np.ndarray, ref: np.ndarray) -> float:
+    """max over rows t of ( max_i |y[t,i]-ref[t,i]| / max_i |ref[t,i]| ): the same metric taken
+    token by token, so that a token whose output is small cannot hide behind a large one.
+    Rows of ref that are entirely zero are compared absolutely (their error must be zero to pass)."""
+    y = np.asarray(y, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    y = y.reshape(-1, y.shape[-1])
+    ref = ref.reshape(-1, ref.shape[-1])
+    d = np.abs(y - ref).max(axis=1)
+    m = np.abs(ref).max(axis=1)
+    rel = np.where(m > 0, d / np.where(m > 0, m, 1.0), np.where(d > 0, np.inf, 0.0))
+    return float(rel.max()) if rel.size else 0.0
+
+
+def route_margins(logits: np.ndarray, bias: Optional[np.ndarray], spec: LayerSpec) -> Tuple[np.ndarray, np.ndarray]:
+    """How close each token's selection is to a different outcome, in units of fp32 spacing.
+
+    Returns (expert_margin [T], group_margin [T]): the gap between the K-th selected and the
+    best unselected selection score among the kept groups, and between the last kept and the
+    best dropped group score (inf when nothing is dropped), each divided by the fp32 spacing
+    (ulp) at the larger of the two magnitudes.  A margin of 0 is an exact tie (decided by the
+    index rule); margins of a few ulp mark tokens whose ids would change under a one-ulp
+    difference of the sigmoid between two exp implementations.  Uses the same score
+    definitions as route().
+    """
+    z = np.asarray(logits, dtype=np.float32)
+    T, E = z.shape
+    gs = E // spec.n_group
+    em = np.full(T, np.inf)
+    gm = np.full(T, np.inf)
+
+    def ulps(a, b):
+        big = np.float32(max(abs(float(a)), abs(float(b)), np.finfo(np.float32).tiny))
+        return abs(float(a) - float(b)) / float(np.spacing(big))
+
+    for t in range(T):
+        if spec.score_fn == SCORE_SIGMOID:
+            s = (1.0 / (1.0 + np.exp(-z[t].astype(np.float64)))).astype(np.float32)
+            c = (s + bias.astype(np.float32)).astype(np.float32) if bias is not None else s
+        else:
+            c = z[t]
+        allowed = np.ones(E, dtype=bool)
+        if spec.n_group > 1:
+            gscore = np.zeros(spec.n_group, dtype=np.float32)
+            for g in range(spec.n_group):
+                top = np.sort(c[g * gs:(g + 1) * gs])[::-1]
+                gscore[g] = np.float32(top[0]) + np.float32(top[1])
+            order = _argsort_desc_stable(gscore)
+            if spec.topk_group < spec.n_group:
+                gm[t] = ulps(gscore[order[spec.topk_group - 1]], gscore[order[spec.topk_group]])
+            allowed[:] = False
+            for g in order[:spec.topk_group]:
+                allowed[g * gs:(g + 1) * gs] = True
+        cand = np.sort(c[allowed])[::-1]
+        if len(cand) > spec.K:
+            em[t] = ulps(cand[spec.K - 1], cand[spec.K])
+    return em, gm

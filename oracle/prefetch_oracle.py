@@ -26,16 +26,15 @@ def copy_plan(prefetch_size: Sequence[int], peers: Sequence[int], slice_bytes: i
     peers the inner loop, so consecutive copies come from different source ranks.
     """
     assert slice_bytes > 0
+    n_peers = len(peers)
     plan = []
     for p, M in enumerate(prefetch_size):
-        offset = 0
-        while offset < M:
-            chunk = min(slice_bytes, M - offset)
-            for peer in peers:
-                src = src_base[peer][p] + offset
-                dst = dst_base[peer][p] + offset
-                plan.append((dst, src, chunk))
-            offset += slice_bytes
+        # Copy i of this parameter moves slice i // n_peers of the pull from peer i % n_peers:
+        # the slice index changes slowest, so each round of n_peers copies visits every source once.
+        for i in range(n_slices(M, slice_bytes) * n_peers):
+            k, q = divmod(i, n_peers)
+            lo = k * slice_bytes
+            plan.append((dst_base[peers[q]][p] + lo, src_base[peers[q]][p] + lo, min(slice_bytes, M - lo)))
     return plan
 
 
