@@ -12,8 +12,9 @@
  *   - Every data pointer is DEVICE memory owned by the caller unless marked HOST.  The
  *     library never frees caller memory; it allocates its own workspace in dwdp_create.
  *   - Calls enqueue work on the context's compute stream (or its private copy stream for
- *     dwdp_prefetch_layer) and return without waiting.  Buffers must stay valid until
- *     the stream has passed the call.  dwdp_moe_forward may run part of its grouped GEMM
+ *     dwdp_prefetch_layer) and return without waiting on the device.  Buffers must stay valid
+ *     until the stream has passed the call.  Calls that allocate (dwdp_create, and the first
+ *     dwdp_prefetch_layer / dwdp_prepare_prefetch with given arguments in copy-kernel mode) say so.  dwdp_moe_forward may run part of its grouped GEMM
  *     on a second private stream; that work is forked from and joined back into the
  *     compute stream with events, so callers only ever order against the compute stream.
  *   - Errors are return codes; argument errors are detected on the host before anything
@@ -114,7 +115,9 @@ dwdp_status dwdp_route(dwdp_ctx* ctx, const float* logits, const float* bias, in
                        int32_t* topk_ids, float* topk_w);
 
 /*
- * Permutation by expert: stable counting sort of f = t*K + k by topk_ids[f].
+ * Permutation by expert (the paper names no sorting rule; grouped GEMMs over per-expert row
+ * ranges, its Section 4.2, need rows grouped by expert, and the stable order makes the
+ * result unique): stable counting sort of f = t*K + k by topk_ids[f].
  *   expert_offsets int32 [E+1 (+1 if has_shared)]  exclusive prefix sums; with a shared
  *                  expert the last entry is T*K + T (its rows are T*K + t)
  *   perm     int32 [T*K]  perm[r] = f of sorted row r
@@ -203,10 +206,23 @@ dwdp_status dwdp_pack_mxfp4_weight(dwdp_ctx* ctx, const void* src_codes, const v
  *     most 256 KiB).  The slice order of the plan is kept, the slice size costs nothing,
  *     and n_workgroups bounds how many compute units the copy takes from the GEMMs.
  *     The device copy of a layer's plan is built on the first call with given arguments
- *     (a synchronous upload) and reused while the arguments stay the same.
+ *     (one pinned-host and one device allocation, an asynchronous upload on the copy stream;
+ *     no wait on any stream) and reused while the arguments stay the same.
+ *     dwdp_prepare_prefetch builds it ahead of time, so that no allocation falls inside the
+ *     pipeline.
  */
 enum { DWDP_COPY_MEMCPY = 0, DWDP_COPY_KERNEL = 1 };
 dwdp_status dwdp_set_copy_engine(dwdp_ctx* ctx, int32_t mode, int32_t n_workgroups);
+
+/*
+ * Set-up half of dwdp_prefetch_layer for the copy-kernel engine: builds (or rebuilds, when the
+ * arguments differ from the cached ones) the device copy of `layer`'s plan and copies nothing.
+ * Same arguments and errors as dwdp_prefetch_layer, without its protocol check.  Calling it
+ * once per layer after the buffers exist keeps every later dwdp_prefetch_layer with the same
+ * arguments free of allocations.  Valid in either engine mode.
+ */
+dwdp_status dwdp_prepare_prefetch(dwdp_ctx* ctx, int32_t layer, const void* const* src, void* const* dst,
+                                  const size_t* bytes, int32_t n_peers, int32_t n_params, size_t slice_bytes);
 
 /*
  * Host-only: the copy plan dwdp_prefetch_layer would issue, written to HOST arrays of
@@ -240,11 +256,11 @@ dwdp_status dwdp_merge_experts(dwdp_ctx* ctx, int32_t layer, const dwdp_expert_p
  * synchronises, adds up the elapsed milliseconds per stage over the calls since the last
  * read into ms_sum[DWDP_N_STAGES] (HOST), stores the number of calls in *n_calls and
  * resets.  At most DWDP_PROFILE_MAX_CALLS calls are kept between reads.
- * With FP8 weights the grouped GEMMs run as two concurrent chains: GEMM1/GEMM2 are the
- * weight-streaming kernels on the compute stream (GEMM2 also contains the wait for the
- * other chain), GEMM1_TILE/GEMM2_TILE the LDS-tiled kernels on an internal stream (on the
- * compute stream when no expert can be streamed); QUANT includes building the tile list
- * and any wait for prefetched experts.
+ * With FP8 weights the grouped GEMMs run as two concurrent chains: GEMM1_TILE/GEMM2_TILE are
+ * the LDS-tiled kernels on the compute stream, GEMM1/GEMM2 the weight-streaming kernels on an
+ * internal stream forked from and joined back into it (on the compute stream when no expert
+ * can be tiled); QUANT is the time between the permutation's end and the first GEMM (any wait
+ * for prefetched experts).
  */
 enum {
   DWDP_STAGE_ROUTE = 0,

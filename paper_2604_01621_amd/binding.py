@@ -55,6 +55,7 @@ def _load() -> C.CDLL:
     lib.dwdp_permute.argtypes = [vp, vp, i32, vp, vp, vp]
     lib.dwdp_moe_forward.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp]
     lib.dwdp_prefetch_layer.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(sz), i32, i32, sz]
+    lib.dwdp_prepare_prefetch.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(sz), i32, i32, sz]
     lib.dwdp_build_copy_plan.argtypes = [C.POINTER(vp), C.POINTER(vp), C.POINTER(sz), i32, i32, sz,
                                          C.POINTER(vp), C.POINTER(vp), C.POINTER(sz), sz, C.POINTER(sz)]
     lib.dwdp_merge_experts.argtypes = [vp, i32, C.POINTER(dwdp_expert_ptrs), i32, vp, vp, vp, vp,
@@ -173,6 +174,15 @@ class Context:
         a_dst = (vp * max(n, 1))(*[vp(v) for v in dst])
         a_b = (sz * max(n_params, 1))(*nbytes)
         self._check(lib.dwdp_prefetch_layer(self.h, layer, a_src, a_dst, a_b, n_peers, n_params, slice_bytes))
+
+    def dwdp_prepare_prefetch(self, layer, src: Sequence[int], dst: Sequence[int], nbytes: Sequence[int], n_peers: int,
+                              n_params: int, slice_bytes: int):
+        vp, sz = C.c_void_p, C.c_size_t
+        n = n_peers * n_params
+        a_src = (vp * max(n, 1))(*[vp(v) for v in src])
+        a_dst = (vp * max(n, 1))(*[vp(v) for v in dst])
+        a_b = (sz * max(n_params, 1))(*nbytes)
+        self._check(lib.dwdp_prepare_prefetch(self.h, layer, a_src, a_dst, a_b, n_peers, n_params, slice_bytes))
 
     def dwdp_merge_experts(self, layer: int, table_host: torch.Tensor, w13_out, s13_out, w2_out,
                            s2_out) -> torch.Tensor:

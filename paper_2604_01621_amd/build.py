@@ -32,8 +32,7 @@ def sources():
 
 def build(verbose: bool = False) -> str:
     """Compile every source (always; the caller decides when) and return the library path."""
-    extra = os.environ.get("DWDP_EXTRA_HIPCC_FLAGS", "").split()   # experiments only
-    cmd = [hipcc_path()] + HIPCC_FLAGS + extra + sources() + ["-o", LIB + ".tmp"]
+    cmd = [hipcc_path()] + HIPCC_FLAGS + sources() + ["-o", LIB + ".tmp"]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)

@@ -34,11 +34,18 @@ struct dwdp_ctx {
   int copy_mode = 0;
   int copy_wgs = 256;
   struct PlanCache {
-    std::vector<uintptr_t> key;  // the arguments the cached plan was built from
-    CopyUnit* units = nullptr;   // device
+    std::vector<uintptr_t> key;      // the arguments the cached plan was built from
+    bool valid = false;
+    CopyUnit* units = nullptr;       // device
+    CopyUnit* units_host = nullptr;  // pinned host image the device copy is uploaded from
     int n_units = 0;
   };
   std::vector<PlanCache> plan_cache;  // per layer
+  struct Retired {
+    CopyUnit* units;
+    CopyUnit* units_host;
+  };
+  std::vector<Retired> retired;  // replaced plans, freed at destroy
   // double-buffer protocol
   std::vector<hipEvent_t> staged_ev;  // per layer: its prefetch copies are complete
   hipEvent_t done_ev[2] = {nullptr, nullptr};  // per staging buffer: its last reader finished
@@ -175,8 +182,14 @@ extern "C" void dwdp_destroy(dwdp_ctx* c) {
   if (c->mt_expert) (void)hipFree(c->mt_expert);
   if (c->mt_row0) (void)hipFree(c->mt_row0);
   if (c->n_mtiles) (void)hipFree(c->n_mtiles);
-  for (auto& pc : c->plan_cache)
+  for (auto& pc : c->plan_cache) {
     if (pc.units) (void)hipFree(pc.units);
+    if (pc.units_host) (void)hipHostFree(pc.units_host);
+  }
+  for (auto& r : c->retired) {
+    if (r.units) (void)hipFree(r.units);
+    if (r.units_host) (void)hipHostFree(r.units_host);
+  }
   for (hipEvent_t ev : c->staged_ev)
     if (ev) (void)hipEventDestroy(ev);
   for (hipEvent_t ev : c->done_ev)
@@ -279,6 +292,8 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
     if (consume) ctx->pending_layer[b] = -1;
     return DWDP_OK;
   }
+  bool forked = false, released = false;
+  auto enqueue = [&]() -> dwdp_status {
   const bool prof = ctx->prof && ctx->prof_calls < DWDP_PROFILE_MAX_CALLS;
   int32_t* ids = (int32_t*)ctx->ws[DWDP_WS_TOPK_IDS];
   float* tw = (float*)ctx->ws[DWDP_WS_TOPK_W];
@@ -323,6 +338,7 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
   if (two) {
     HIP_TRY(ctx, hipEventRecord(ctx->fork_ev, s));
     HIP_TRY(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_ev, 0));
+    forked = true;
   }
   if (fp8) {
     if (use_stream) {
@@ -356,7 +372,10 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
                             ctx->ws[DWDP_WS_YP], s);
       if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfMain + 3), s));
     }
-    if (two) HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->join_ev, 0));
+    if (two) {
+      HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->join_ev, 0));
+      forked = false;
+    }
   } else {
     if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM1), s));
     launch_gemm1_bf16(ga, x, ctx->ws[DWDP_WS_HQ], s);
@@ -367,6 +386,7 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
   tl_close(ctx, span, s);
   // The layer's weights have been read once GEMM-2 is done: release the staging buffer here.
   HIP_TRY(ctx, hipEventRecord(ctx->done_ev[b], s));
+  released = true;
   ctx->done_valid[b] = true;
   if (consume) ctx->pending_layer[b] = -1;
   if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_COMBINE), s));
@@ -378,7 +398,55 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
   }
   HIP_TRY(ctx, hipGetLastError());
   return DWDP_OK;
+  };
+  st = enqueue();
+  if (st != DWDP_OK) {
+    // A HIP call failed half-way.  Leave the context in a state the next call can start from: the
+    // second chain is joined back into the compute stream, and the staging buffer is released in
+    // stream order (whatever was enqueued has been enqueued; the layer's result is not valid).
+    // The message of the first failure is kept.
+    if (forked && hipEventRecord(ctx->join_ev, ctx->aux) == hipSuccess) (void)hipStreamWaitEvent(s, ctx->join_ev, 0);
+    if (!released && hipEventRecord(ctx->done_ev[b], s) == hipSuccess) ctx->done_valid[b] = true;
+    if (consume) ctx->pending_layer[b] = -1;
+    (void)hipGetLastError();
+  }
+  return st;
 }
+
+// The copy plan of paper Section 4.3.2 (Listing 1) in issue order, produced one entry at a time:
+// parameters in turn; within a parameter the slices in turn; within a slice every peer once, in
+// the caller's order.  Entry = (index into src/dst, byte offset inside the region, bytes).
+namespace {
+struct PlanWalk {
+  const size_t* bytes;
+  int n_peers, n_params;
+  size_t slice;
+  int p = 0, peer = 0;
+  size_t off = 0;
+  PlanWalk(const size_t* b, int peers, int params, size_t s) : bytes(b), n_peers(peers), n_params(params), slice(s) {
+    skip_empty();
+  }
+  void skip_empty() {
+    while (p < n_params && (bytes[p] == 0 || n_peers == 0)) p++;
+  }
+  bool done() const { return p >= n_params; }
+  size_t region() const { return (size_t)peer * n_params + p; }
+  size_t chunk() const {
+    const size_t left = bytes[p] - off;
+    return slice && slice < left ? slice : left;
+  }
+  void advance() {
+    if (++peer < n_peers) return;
+    peer = 0;
+    off += chunk();
+    if (off >= bytes[p]) {
+      off = 0;
+      p++;
+      skip_empty();
+    }
+  }
+};
+}  // namespace
 
 extern "C" dwdp_status dwdp_build_copy_plan(const void* const* src, void* const* dst, const size_t* bytes,
                                             int32_t n_peers, int32_t n_params, size_t slice_bytes, void** plan_dst,
@@ -386,90 +454,105 @@ extern "C" dwdp_status dwdp_build_copy_plan(const void* const* src, void* const*
   if (!src || !dst || !bytes || !n_out || n_peers < 0 || n_params < 0) return DWDP_EINVAL;
   if (cap > 0 && (!plan_dst || !plan_src || !plan_bytes)) return DWDP_EINVAL;
   size_t n = 0;
-  for (int p = 0; p < n_params; p++) {
-    const size_t M = bytes[p];
-    const size_t s = slice_bytes ? slice_bytes : (M ? M : 1);
-    for (size_t offset = 0; offset < M; offset += s) {
-      const size_t chunk = M - offset < s ? M - offset : s;
-      for (int peer = 0; peer < n_peers; peer++) {
-        const size_t idx = (size_t)peer * n_params + p;
-        if (n < cap) {
-          plan_dst[n] = (char*)dst[idx] + offset;
-          plan_src[n] = (const char*)src[idx] + offset;
-          plan_bytes[n] = chunk;
-        }
-        n++;
-      }
-    }
+  for (PlanWalk w(bytes, n_peers, n_params, slice_bytes); !w.done(); w.advance(), n++) {
+    if (n >= cap) continue;
+    plan_dst[n] = (char*)dst[w.region()] + w.off;
+    plan_src[n] = (const char*)src[w.region()] + w.off;
+    plan_bytes[n] = w.chunk();
   }
   *n_out = n;
   return DWDP_OK;
+}
+
+static dwdp_status check_prefetch_args(dwdp_ctx* ctx, int32_t layer, const void* const* src, void* const* dst,
+                                       const size_t* bytes, int32_t n_peers, int32_t n_params) {
+  if (layer < 0 || layer >= ctx->cfg.n_layers)
+    return fail(ctx, DWDP_EINVAL, "layer %d outside [0,%d)", layer, ctx->cfg.n_layers);
+  if (!src || !dst || !bytes || n_peers < 0 || n_params < 0)
+    return fail(ctx, DWDP_EINVAL, "prefetch: NULL pointer or negative count");
+  for (int i = 0; i < n_peers * n_params; i++)
+    if (bytes[i % n_params] && (!src[i] || !dst[i])) return fail(ctx, DWDP_EINVAL, "NULL region pointer at %d", i);
+  return DWDP_OK;
+}
+
+// Device copy of a layer's plan for the copy-plan kernel, cut into units of at most 256 KiB so
+// that the workgroups share evenly.  Built when the arguments differ from the cached ones: the
+// units are written into a pinned host array and uploaded with an asynchronous copy on the copy
+// stream, i.e. ordered before the kernel that reads them and after earlier launches that read
+// the previous plan (same stream); nothing waits on the host.  A replaced plan's buffers are
+// kept until dwdp_destroy (an upload or a launch may still be reading them).
+static dwdp_status ensure_device_plan(dwdp_ctx* ctx, int32_t layer, const void* const* src, void* const* dst,
+                                      const size_t* bytes, int32_t n_peers, int32_t n_params, size_t slice_bytes) {
+  std::vector<uintptr_t> key;
+  key.push_back((uintptr_t)n_peers);
+  key.push_back((uintptr_t)n_params);
+  key.push_back((uintptr_t)slice_bytes);
+  for (int i = 0; i < n_peers * n_params; i++) {
+    key.push_back((uintptr_t)src[i]);
+    key.push_back((uintptr_t)dst[i]);
+  }
+  for (int p = 0; p < n_params; p++) key.push_back((uintptr_t)bytes[p]);
+  dwdp_ctx::PlanCache& pc = ctx->plan_cache[layer];
+  if (pc.valid && pc.key == key) return DWDP_OK;
+  constexpr size_t kUnit = 256 << 10;
+  size_t n_units = 0;
+  for (PlanWalk w(bytes, n_peers, n_params, slice_bytes); !w.done(); w.advance())
+    n_units += (w.chunk() + kUnit - 1) / kUnit;
+  if (n_units > (size_t)1 << 30) return fail(ctx, DWDP_ESHAPE, "copy plan of %zu units is too long", n_units);
+  if (pc.units) ctx->retired.push_back({pc.units, pc.units_host});
+  pc.units = nullptr;
+  pc.units_host = nullptr;
+  pc.valid = false;
+  pc.n_units = 0;
+  if (n_units) {
+    HIP_TRY(ctx, hipHostMalloc((void**)&pc.units_host, n_units * sizeof(CopyUnit), hipHostMallocDefault));
+    HIP_TRY(ctx, hipMalloc((void**)&pc.units, n_units * sizeof(CopyUnit)));
+    size_t u = 0;
+    for (PlanWalk w(bytes, n_peers, n_params, slice_bytes); !w.done(); w.advance())
+      for (size_t o = 0, c = w.chunk(); o < c; o += kUnit)
+        pc.units_host[u++] = CopyUnit{(char*)dst[w.region()] + w.off + o, (const char*)src[w.region()] + w.off + o,
+                                      c - o < kUnit ? c - o : kUnit};
+    HIP_TRY(ctx, hipMemcpyAsync(pc.units, pc.units_host, n_units * sizeof(CopyUnit), hipMemcpyHostToDevice, ctx->copy));
+  }
+  pc.n_units = (int)n_units;
+  pc.key = key;
+  pc.valid = true;
+  return DWDP_OK;
+}
+
+extern "C" dwdp_status dwdp_prepare_prefetch(dwdp_ctx* ctx, int32_t layer, const void* const* src, void* const* dst,
+                                             const size_t* bytes, int32_t n_peers, int32_t n_params,
+                                             size_t slice_bytes) {
+  if (!ctx) return DWDP_EINVAL;
+  dwdp_status st = check_prefetch_args(ctx, layer, src, dst, bytes, n_peers, n_params);
+  if (st != DWDP_OK) return st;
+  return ensure_device_plan(ctx, layer, src, dst, bytes, n_peers, n_params, slice_bytes);
 }
 
 extern "C" dwdp_status dwdp_prefetch_layer(dwdp_ctx* ctx, int32_t layer, const void* const* src, void* const* dst,
                                            const size_t* bytes, int32_t n_peers, int32_t n_params,
                                            size_t slice_bytes) {
   if (!ctx) return DWDP_EINVAL;
-  if (layer < 0 || layer >= ctx->cfg.n_layers)
-    return fail(ctx, DWDP_EINVAL, "layer %d outside [0,%d)", layer, ctx->cfg.n_layers);
-  if (!src || !dst || !bytes || n_peers < 0 || n_params < 0)
-    return fail(ctx, DWDP_EINVAL, "dwdp_prefetch_layer: NULL pointer or negative count");
-  for (int i = 0; i < n_peers * n_params; i++)
-    if (bytes[i % n_params] && (!src[i] || !dst[i])) return fail(ctx, DWDP_EINVAL, "NULL region pointer at %d", i);
+  dwdp_status st = check_prefetch_args(ctx, layer, src, dst, bytes, n_peers, n_params);
+  if (st != DWDP_OK) return st;
   const int b = layer & 1;
   if (ctx->pending_layer[b] != -1)
     return fail(ctx, DWDP_ESTATE, "staging buffer %d still holds layer %d, which no dwdp_moe_forward has consumed", b,
                 ctx->pending_layer[b]);
-  size_t n = 0;
-  dwdp_status st = dwdp_build_copy_plan(src, dst, bytes, n_peers, n_params, slice_bytes, nullptr, nullptr, nullptr, 0,
-                                        &n);
-  if (st != DWDP_OK) return fail(ctx, st, "copy plan");
-  std::vector<void*> pd(n);
-  std::vector<const void*> ps(n);
-  std::vector<size_t> pb(n);
-  dwdp_build_copy_plan(src, dst, bytes, n_peers, n_params, slice_bytes, pd.data(), ps.data(), pb.data(), n, &n);
+  if (ctx->copy_mode == DWDP_COPY_KERNEL) {
+    st = ensure_device_plan(ctx, layer, src, dst, bytes, n_peers, n_params, slice_bytes);
+    if (st != DWDP_OK) return st;
+  }
   // double buffering: the buffer is free once its previous reader has finished
   if (ctx->done_valid[b]) HIP_TRY(ctx, hipStreamWaitEvent(ctx->copy, ctx->done_ev[b], 0));
-  if (ctx->copy_mode == DWDP_COPY_KERNEL) {
-    // The plan of a layer is static (same regions every iteration): build its device copy once.
-    std::vector<uintptr_t> key;
-    key.push_back((uintptr_t)n_peers);
-    key.push_back((uintptr_t)n_params);
-    key.push_back((uintptr_t)slice_bytes);
-    for (int i = 0; i < n_peers * n_params; i++) {
-      key.push_back((uintptr_t)src[i]);
-      key.push_back((uintptr_t)dst[i]);
-    }
-    for (int p = 0; p < n_params; p++) key.push_back((uintptr_t)bytes[p]);
-    dwdp_ctx::PlanCache& pc = ctx->plan_cache[layer];
-    if (pc.key != key) {
-      // plan entries are cut into units of at most 256 KiB so that the workgroups share evenly
-      const size_t unit = 256 << 10;
-      std::vector<CopyUnit> units;
-      for (size_t i = 0; i < n; i++)
-        for (size_t o = 0; o < pb[i]; o += unit)
-          units.push_back(CopyUnit{(char*)pd[i] + o, (const char*)ps[i] + o, pb[i] - o < unit ? pb[i] - o : unit});
-      if (pc.units) {
-        HIP_TRY(ctx, hipStreamSynchronize(ctx->copy));  // an earlier launch may still read the old plan
-        HIP_TRY(ctx, hipFree(pc.units));
-        pc.units = nullptr;
-      }
-      pc.key.clear();
-      if (!units.empty()) {
-        HIP_TRY(ctx, hipMalloc((void**)&pc.units, units.size() * sizeof(CopyUnit)));
-        HIP_TRY(ctx, hipMemcpy(pc.units, units.data(), units.size() * sizeof(CopyUnit), hipMemcpyHostToDevice));
-      }
-      pc.n_units = (int)units.size();
-      pc.key = key;
-    }
-  }
   const int span = tl_open(ctx, DWDP_SPAN_COPY, layer, ctx->copy);
   if (ctx->copy_mode == DWDP_COPY_KERNEL) {
     launch_copy_plan(ctx->plan_cache[layer].units, ctx->plan_cache[layer].n_units, ctx->copy_wgs, ctx->copy);
     HIP_TRY(ctx, hipGetLastError());
   } else {
-    for (size_t i = 0; i < n; i++)
-      HIP_TRY(ctx, hipMemcpyAsync(pd[i], ps[i], pb[i], hipMemcpyDeviceToDevice, ctx->copy));
+    for (PlanWalk w(bytes, n_peers, n_params, slice_bytes); !w.done(); w.advance())
+      HIP_TRY(ctx, hipMemcpyAsync((char*)dst[w.region()] + w.off, (const char*)src[w.region()] + w.off, w.chunk(),
+                                  hipMemcpyDeviceToDevice, ctx->copy));
   }
   tl_close(ctx, span, ctx->copy);
   HIP_TRY(ctx, hipEventRecord(ctx->staged_ev[layer], ctx->copy));

@@ -60,15 +60,6 @@
 
 #include "dwdp_kernels.h"
 
-// Timing experiments only (results are wrong when set): 1 = skip the MFMA/VALU work,
-// 16 = no per-block wait and barrier, 128 = no global loads or copies at all, 4 = no weight
-// loads, 8 = no token copies, 512 = every workgroup reads the same (L2-resident) weight panel,
-// 1024 = print the shader clock of one workgroup (cycle counter over the 100 MHz counter).
-// Never set in a product build.
-#ifndef DWDP_TILE_DBG
-#define DWDP_TILE_DBG 0
-#endif
-
 namespace dwdp {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
@@ -164,11 +155,6 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   __shared__ int32_t lds_row[kSaLen];
   __shared__ __attribute__((aligned(16))) uint8_t lds_epi[kEpiBytes];  // amax / store staging
 
-  long long dbg_c0 = 0, dbg_w0 = 0, dbg_wait_vm = 0, dbg_wait_bar = 0;
-  if (DWDP_TILE_DBG & 1024) {
-    dbg_c0 = clock64();
-    dbg_w0 = wall_clock64();
-  }
   const int xcd = blockIdx.x & 7;
   const int s = blockIdx.x >> 3;
   const int n_mt = *n_mtiles;
@@ -219,9 +205,7 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
       tr = (j == 0 ? 0 : I / 16) + panel * 8 + wave;
     else
       tr = min(panel * 16 + wave * 2 + j, n_tile_rows - 1);
-    if (DWDP_TILE_DBG & 512) tr = G1 ? (j == 0 ? 0 : I / 16) + wave : wave * 2 + j;  // every workgroup reads panel 0
-    a_src[j] = ((DWDP_TILE_DBG & 512) ? (const uint8_t*)(G1 ? table[0].w13 : table[0].w2) : wbase) +
-               (size_t)tr * nkb * kABytes;  // wave-uniform
+    a_src[j] = wbase + (size_t)tr * nkb * kABytes;  // wave-uniform
     sw[j] = sbase + (size_t)(tr / 8) * nkb;  // 8 tiles of 16 rows per 128-row scale block (FP8 weights)
     ms_src[j] = (const uint8_t*)sbase + (size_t)tr * ((nkb + 3) >> 2) * 256;  // packed E8M0 scales (MXFP4 weights)
   }
@@ -293,14 +277,13 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   // reads one or two floats past a token's row: the next row's, or the padding the workspace
   // keeps behind the array).
   auto issue_op = [&](int op, int pos, int img, AFrag& a) __attribute__((always_inline)) {
-    if (DWDP_TILE_DBG & 128) return;
     const int kb = min(pos, nkb - 1);
     if (op < kBP) {
       const int c = min(wave + kTileWaves * op, kBPieces - 1);
-      if (!(DWDP_TILE_DBG & 8)) dma16(act + (b_src[op] + (uint32_t)kb * 128), img_off[img] + c * 1024);
+      dma16(act + (b_src[op] + (uint32_t)kb * 128), img_off[img] + c * 1024);
     } else if (op == kBP) {
-      if (!(DWDP_TILE_DBG & 8)) dma12(act_s + (sa_src + (uint32_t)kb), sg_off[(pos / 3) & 1]);
-    } else if (!(DWDP_TILE_DBG & 4)) {
+      dma12(act_s + (sa_src + (uint32_t)kb), sg_off[(pos / 3) & 1]);
+    } else {
       const int w = op - kBP - 1;  // FP8: 0..3 = (c, half); MXFP4: codes of half 0, half 1, scales of half 0, half 1
       if (!MX) {
         const uint8_t* base = a_src[0] + (size_t)kb * kABytes;  // wave-uniform: scalar registers
@@ -398,7 +381,6 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
     // 16..31 with s1.  Whole-vector read and write of the accumulator: element-wise stores
     // into it under conditions keep the compiler from holding the array in registers.
     auto fold = [&](int t, const v16f& p, float s0, float s1) __attribute__((always_inline)) {
-      if (DWDP_TILE_DBG & 1) return;
       v16f av = acc[t];
 #pragma unroll
       for (int i = 0; i < 8; i++) av[i] = fmaf(p[i], s0, av[i]);
@@ -430,9 +412,9 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
     auto tile = [&](auto t_const) __attribute__((always_inline)) {
       constexpr int t = decltype(t_const)::value;
       bq[1] = read_b(t, 1);
-      if (!(DWDP_TILE_DBG & 1)) pr = mfma(af0, bq[0], zero, ms0);
+      pr = mfma(af0, bq[0], zero, ms0);
       if constexpr (t + 1 < kTT) bq[0] = read_b(t + 1, 0);
-      if (!(DWDP_TILE_DBG & 1)) pr = mfma(af1, bq[1], pr, ms1);
+      pr = mfma(af1, bq[1], pr, ms1);
       scale_products(sa[t % 2], sp0, sp1);
       fold(t, pr, sp0, sp1);
       if constexpr (t + 2 < kTT) sa[t % 2] = read_s(t + 2);
@@ -457,19 +439,11 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   // issue overwrites": own copies complete (in-order counter), then one barrier.
   // n_next: operations of the following block's fetch, the only ones that may be outstanding
   auto publish = [&](auto n_next) {
-    if (DWDP_TILE_DBG & 16) return;
     // pinned between scheduling barriers: nothing of the following issue (its address
     // arithmetic reuses registers of retired loads) may move above the wait
     __builtin_amdgcn_sched_barrier(0);
-    long long tw0 = 0, tw1 = 0;
-    if (DWDP_TILE_DBG & 1024) tw0 = clock64();
     __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(decltype(n_next)::value));
-    if (DWDP_TILE_DBG & 1024) {
-      tw1 = clock64();
-      dbg_wait_vm += tw1 - tw0;
-    }
     __builtin_amdgcn_s_barrier();
-    if (DWDP_TILE_DBG & 1024) dbg_wait_bar += clock64() - tw1;
     __builtin_amdgcn_sched_barrier(0);
   };
 
@@ -477,12 +451,6 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
     asm volatile("" ::"v"(a.t[0][0]), "v"(a.t[0][1]), "v"(a.t[1][0]), "v"(a.t[1][1]), "v"(a.s[0]), "v"(a.s[1]));
   };
   AFrag a0 = {}, a1 = {}, a2 = {};
-  if (DWDP_TILE_DBG & (4 | 128)) {  // timing experiments without weight loads: operands the compiler cannot fold
-    auto opaque = [](AFrag& a) { asm volatile("" : "+v"(a.t[0][0]), "+v"(a.t[0][1]), "+v"(a.t[1][0]), "+v"(a.t[1][1])); };
-    opaque(a0);
-    opaque(a1);
-    opaque(a2);
-  }
   using std::integral_constant;
   using I0 = integral_constant<int, 0>;
   using I1 = integral_constant<int, 1>;
@@ -512,13 +480,6 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   keep(a2);
   __builtin_amdgcn_sched_barrier(0);
   __syncthreads();
-  if ((DWDP_TILE_DBG & 1024) && (threadIdx.x & 63) == 0 && blockIdx.x == 1001) {
-    const long long dc = clock64() - dbg_c0, dw = wall_clock64() - dbg_w0;
-    printf("tile kernel G1=%d block %d wave %d: %lld cycles, %lld ticks of 10 ns -> %.0f MHz, %d K blocks, vm wait %lld, "
-           "barrier wait %lld, ntt %d\n",
-           (int)G1, (int)blockIdx.x, (int)(threadIdx.x >> 6), dc, dw, (double)dc / (double)dw * 100.0, nkb, dbg_wait_vm,
-           dbg_wait_bar, ntt);
-  }
 
   // Accumulator layout of the 32x32 result: this lane holds token ln of every tile and, in
   // register 4q + i (q = 0..3, i = 0..3), row 8q + 4lg + i of the wave's 32 rows.

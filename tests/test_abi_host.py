@@ -68,3 +68,4 @@ def test_create_rejects_bad_shapes_without_gpu():
         assert not h.value
     assert lib.dwdp_create(None, None, C.byref(h)) == binding.EINVAL
     assert lib.dwdp_route(None, None, None, 0, None, None) == binding.EINVAL
+

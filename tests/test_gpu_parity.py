@@ -145,6 +145,7 @@ def _layer_case(binding, cfg, x, logits, bias, w, check_intermediates=False, str
     spec = mo.spec_from(cfg)
     ref = mo.moe_forward(to_np(x), to_np(logits), to_np(bias), experts_numpy(w), spec)
     err, l2 = mo.error_metrics(y.float().cpu().numpy(), ref)
+    assert mo.error_metric_rows(y.float().cpu().numpy(), ref) <= tolerance(cfg)     # token by token as well
     print(f"  T={cfg.T} H={cfg.H} I={cfg.I} E={cfg.E}: max-rel {err:.3e} l2-rel {l2:.3e}", flush=True)
     assert np.isfinite(y.float().cpu().numpy()).all()
     assert err <= tolerance(cfg), (err, l2)

@@ -87,6 +87,38 @@ def test_pipeline_poisoned_and_delayed(env, slice_bytes, engine):
             np.testing.assert_array_equal(got, ref[l].float().cpu().numpy())
 
 
+@pytest.mark.parametrize("engine", [0, 1])
+@pytest.mark.parametrize("smr", [0, 16, 1 << 30])
+def test_buffer_not_overwritten_before_its_reader_is_done(env, smr, engine):
+    """Write-after-read half of the double-buffer protocol (paper Section 2: a staging buffer is
+    reused only once the MoE block that reads it is done).  The compute stream is held back by a
+    bounded spin so that layer 0's GEMMs have not started when layer 2's prefetch -- other
+    weights, same buffer -- is issued; the test itself orders nothing: only the library's wait
+    for the buffer's reader keeps layer 0 from reading layer 2's experts.  Run for every kernel
+    family split (the second chain's end is part of "done")."""
+    binding, pipeline, cfg, ctx, layers, xs, lgs, bs = env
+    print("write-after-read, stream_max_rows", smr, "engine", engine, flush=True)
+    ctx.dwdp_set_stream_max_rows(smr)
+    ctx.dwdp_set_copy_engine(engine, 24)
+    try:
+        ref = _reference_outputs(ctx, cfg, layers, xs, lgs, bs)
+        y0 = torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device="cuda")
+        y2 = torch.empty_like(y0)
+        torch.cuda.synchronize()
+        layers.prefetch(ctx, 0, 4096)
+        torch.cuda._sleep(60_000_000)              # compute stream (the context's: the default stream) held back
+        ctx.dwdp_moe_forward(0, xs[0], lgs[0], bs[0], layers.tables[0], y0)
+        layers.prefetch(ctx, 2, 4096)              # same staging buffer, issued while layer 0 is still waiting to run
+        ctx.dwdp_moe_forward(2, xs[2], lgs[2], bs[2], layers.tables[2], y2)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(y0.float().cpu().numpy(), ref[0].float().cpu().numpy())
+        np.testing.assert_array_equal(y2.float().cpu().numpy(), ref[2].float().cpu().numpy())
+        assert not np.array_equal(ref[0].float().cpu().numpy(), ref[2].float().cpu().numpy())
+    finally:
+        ctx.dwdp_set_stream_max_rows(16)
+        ctx.dwdp_set_copy_engine(0)
+
+
 def test_pipeline_layers_match_oracle(env):
     binding, pipeline, cfg, ctx, layers, xs, lgs, bs = env
     print("pipeline vs oracle", flush=True)
@@ -101,6 +133,7 @@ def test_pipeline_layers_match_oracle(env):
     for l in range(N_LAYERS):
         ref = mo.moe_forward(to_np(xs[l]), to_np(lgs[l]), to_np(bs[l]), experts_numpy(layers.logical[l]), spec)
         err, l2 = mo.error_metrics(ys[l].float().cpu().numpy(), ref)
+        assert mo.error_metric_rows(ys[l].float().cpu().numpy(), ref) <= tolerance(cfg)     # token by token as well
         print(f"  layer {l}: max-rel {err:.3e}", flush=True)
         assert err <= tolerance(cfg)
 
@@ -195,7 +228,7 @@ def test_non_divisible_group_with_redundant_experts(gpu_device):
     ctx.dwdp_set_copy_engine(1, 16)
     for b in range(2):
         layers.poison_staging(b)
-    ys, refs = [], []
+    ys, refs, ins = [], [], []
     for l in range(n_layers):
         x = inputs.make_activations(cfg, 310 + l).cuda()
         lg = inputs.make_gate_logits(cfg, x.cpu(), 310 + l).cuda()
@@ -206,10 +239,19 @@ def test_non_divisible_group_with_redundant_experts(gpu_device):
         ctx.dwdp_moe_forward(l, x, lg, None, layers.all_resident_table(l), ref)
         ys.append(y)
         refs.append(ref)
+        ins.append((x, lg))
     torch.cuda.synchronize()
     ctx.dwdp_set_copy_engine(0)
+    spec = mo.spec_from(cfg)
     for l in range(n_layers):
         got = ys[l].float().cpu().numpy()
         assert np.isfinite(got).all()
         np.testing.assert_array_equal(got, refs[l].float().cpu().numpy())
+        # and against the oracle, which knows nothing of placements: the layer's logical weights by value
+        x, lg = ins[l]
+        want = mo.moe_forward(to_np(x), to_np(lg), None, experts_numpy(layers.logical[l]), spec)
+        err, l2 = mo.error_metrics(got, want)
+        rows = mo.error_metric_rows(got, want)
+        print(f"  layer {l}: max-rel {err:.3e} per-row {rows:.3e}", flush=True)
+        assert err <= tolerance(cfg) and rows <= tolerance(cfg)
     ctx.close()

@@ -55,5 +55,6 @@ def test_random_small_layers(gpu_device, sweep_seed):
         got = y.float().cpu().numpy()
         assert np.isfinite(got).all()
         err, l2 = mo.error_metrics(got, ref)
+        assert mo.error_metric_rows(got, ref) <= tolerance(cfg)     # token by token as well
         assert err <= tolerance(cfg), (shape, smr, bias_kind, seed, err, l2)
         ctx.close()
