@@ -129,6 +129,25 @@ dwdp_status dwdp_permute(dwdp_ctx* ctx, const int32_t* topk_ids, int32_t T,
                          int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm);
 
 /*
+ * dwdp_permute for callers that cannot allocate device memory and hold no context: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same outputs as
+ * dwdp_permute for the same topk_ids (bit for bit); E, K, has_shared and the stream (a
+ * hipStream_t, NULL = the default stream) are arguments instead of context state.  The only
+ * scratch of the permutation -- the per-chunk expert histograms of the multi-workgroup path
+ * used when T exceeds one chunk (1024 tokens for E <= 384) -- lives in a static device array of
+ * DWDP_STATIC_SCRATCH_BYTES that every GPU the library runs on holds until the process ends;
+ * the call allocates and frees nothing.  Limits: K <= E <= 1024, K <= 32 and
+ * ceil(T / 128) * E * 4 <= DWDP_STATIC_SCRATCH_BYTES (T <= 131072 at E = 256); DWDP_ESHAPE
+ * beyond them, with the message in dwdp_last_error(NULL).  All calls on one GPU share the array:
+ * calls that may overlap on a GPU (different streams, different threads) race and must be
+ * ordered by the caller.  Nothing in the array has to start at zero (every entry that is read
+ * is written by the same call first).
+ */
+enum { DWDP_STATIC_SCRATCH_BYTES = 1 << 20 };
+dwdp_status dwdp_permute_static(const int32_t* topk_ids, int32_t T, int32_t E, int32_t K, int32_t has_shared,
+                                void* stream, int32_t* expert_offsets, int32_t* perm, int32_t* inv_perm);
+
+/*
  * One MoE layer forward: route -> permute -> (FP8: quantise x per token per 128) ->
  * grouped GEMM gate/up + SwiGLU (FP8: quantise h per token per 128) -> grouped GEMM down
  * -> y[t] = sum_k w[t,k] * out[t,k] (+ shared expert, weight 1).

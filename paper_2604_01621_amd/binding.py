@@ -56,6 +56,7 @@ def _load() -> C.CDLL:
     lib.dwdp_moe_forward.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp]
     lib.dwdp_prefetch_layer.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(sz), i32, i32, sz]
     lib.dwdp_prepare_prefetch.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(sz), i32, i32, sz]
+    lib.dwdp_permute_static.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp]
     lib.dwdp_build_copy_plan.argtypes = [C.POINTER(vp), C.POINTER(vp), C.POINTER(sz), i32, i32, sz,
                                          C.POINTER(vp), C.POINTER(vp), C.POINTER(sz), sz, C.POINTER(sz)]
     lib.dwdp_merge_experts.argtypes = [vp, i32, C.POINTER(dwdp_expert_ptrs), i32, vp, vp, vp, vp,
@@ -122,6 +123,16 @@ def expert_table(weights: ExpertWeights, device=None) -> torch.Tensor:
     # expert_table(ctx.pack_experts(w)) does not leave it pointing at freed (and soon reused) memory.
     t._dwdp_keepalive = weights
     return t
+
+
+def dwdp_permute_static(topk_ids: torch.Tensor, E: int, K: int, has_shared: int, expert_offsets: torch.Tensor,
+                        perm: torch.Tensor, inv_perm: torch.Tensor, stream: Optional[torch.cuda.Stream] = None):
+    """The context-free, allocation-free permutation (see dwdp.h); topk_ids int32 [T,K]."""
+    s = C.c_void_p(stream.cuda_stream) if stream is not None else None
+    st = lib.dwdp_permute_static(_ptr(topk_ids), topk_ids.shape[0], E, K, has_shared, s, _ptr(expert_offsets),
+                                 _ptr(perm), _ptr(inv_perm))
+    if st != OK:
+        raise DwdpError(st, (lib.dwdp_last_error(None) or b"").decode())
 
 
 class Context:

@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -260,6 +261,51 @@ extern "C" dwdp_status dwdp_permute(dwdp_ctx* ctx, const int32_t* topk_ids, int3
   launch_permute(topk_ids, T, ctx->cfg.E, ctx->cfg.K, ctx->cfg.has_shared, ctx->chunk_counts, expert_offsets, perm,
                  inv_perm, nullptr, 0, ctx->compute);
   HIP_TRY(ctx, hipGetLastError());
+  return DWDP_OK;
+}
+
+// ---- the permutation without a context and without any allocation ----
+// Scratch of dwdp_permute_static: the per-chunk expert histograms of the multi-workgroup
+// permutation.  One copy per GPU, held until the process ends; every call on a GPU uses it.
+__device__ __align__(256) static int32_t scratch[DWDP_STATIC_SCRATCH_BYTES / 4];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+int32_t* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each GPU, looked up once
+}  // namespace
+
+extern "C" dwdp_status dwdp_permute_static(const int32_t* topk_ids, int32_t T, int32_t E, int32_t K,
+                                           int32_t has_shared, void* stream, int32_t* expert_offsets, int32_t* perm,
+                                           int32_t* inv_perm) {
+  if (T < 0 || E <= 0 || K <= 0 || (has_shared != 0 && has_shared != 1))
+    return fail(nullptr, DWDP_EINVAL, "dwdp_permute_static: negative or zero size");
+  if (E > 1024 || K > E || K > 32) return fail(nullptr, DWDP_ESHAPE, "dwdp_permute_static: need K <= E <= 1024, K <= 32");
+  if ((long)T * K > (1L << 30)) return fail(nullptr, DWDP_ESHAPE, "dwdp_permute_static: T * K too large");
+  if (!expert_offsets) return fail(nullptr, DWDP_EINVAL, "dwdp_permute_static: expert_offsets is NULL");
+  if (T > 0 && (!topk_ids || !perm || !inv_perm)) return fail(nullptr, DWDP_EINVAL, "dwdp_permute_static: NULL pointer");
+  const long chunk = permute_multi_chunk_tokens(E);
+  const long need = T > permute_chunk_tokens(E) ? (T + chunk - 1) / chunk * E * 4 : 0;
+  if (need > (long)DWDP_STATIC_SCRATCH_BYTES)
+    return fail(nullptr, DWDP_ESHAPE, "dwdp_permute_static: T = %d with E = %d needs %ld bytes of scratch, the static "
+                "array holds %d", T, E, need, (int)DWDP_STATIC_SCRATCH_BYTES);
+  int dev = 0;
+  HIP_TRY(nullptr, hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(nullptr, DWDP_ESHAPE, "dwdp_permute_static: device index %d", dev);
+  int32_t* sp;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+      // the array's name is a host-side handle; its address on the current GPU comes from the runtime
+      void* p = nullptr;
+      HIP_TRY(nullptr, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+      if (!p) return fail(nullptr, DWDP_EHIP, "dwdp_permute_static: no device address for the scratch array");
+      g_scratch_ptr[dev] = (int32_t*)p;
+    }
+    sp = g_scratch_ptr[dev];
+  }
+  launch_permute(topk_ids, T, E, K, has_shared, sp, expert_offsets, perm, inv_perm, nullptr, 0, (hipStream_t)stream);
+  HIP_TRY(nullptr, hipGetLastError());
   return DWDP_OK;
 }
 

@@ -69,3 +69,18 @@ def test_create_rejects_bad_shapes_without_gpu():
     assert lib.dwdp_create(None, None, C.byref(h)) == binding.EINVAL
     assert lib.dwdp_route(None, None, None, 0, None, None) == binding.EINVAL
 
+
+def test_permute_static_rejects_bad_arguments_without_gpu():
+    """The allocation-free permutation checks its arguments and its scratch limit before any HIP call."""
+    lib = binding.lib
+    one = C.c_void_p(16)       # any non-NULL value: rejected calls never touch the pointers
+    assert lib.dwdp_permute_static(one, -1, 8, 2, 0, None, one, one, one) == binding.EINVAL
+    assert lib.dwdp_permute_static(one, 4, 0, 2, 0, None, one, one, one) == binding.EINVAL
+    assert lib.dwdp_permute_static(one, 4, 8, 2, 2, None, one, one, one) == binding.EINVAL
+    assert lib.dwdp_permute_static(one, 4, 2048, 2, 0, None, one, one, one) == binding.ESHAPE
+    assert lib.dwdp_permute_static(one, 4, 8, 9, 0, None, one, one, one) == binding.ESHAPE
+    assert lib.dwdp_permute_static(one, 4, 8, 2, 0, None, None, one, one) == binding.EINVAL
+    assert lib.dwdp_permute_static(None, 4, 8, 2, 0, None, one, one, one) == binding.EINVAL
+    # scratch limit: ceil(T / 128) * E * 4 bytes must fit DWDP_STATIC_SCRATCH_BYTES = 1 MiB
+    assert lib.dwdp_permute_static(one, 131072 + 1, 256, 8, 1, None, one, one, one) == binding.ESHAPE
+    assert b"scratch" in lib.dwdp_last_error(None)
