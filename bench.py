@@ -3,14 +3,24 @@
 
 A step is one dwdp_moe_forward (route -> permute -> quantise -> grouped GEMM gate/up+SwiGLU
 -> grouped GEMM down -> combine) over one batch of seeded synthetic tokens with all inputs
-and weights resident in HBM.  Default workload: the DeepSeek-R1-shaped decode layer, T=64.
-Prints ONE JSON line (see the fields below); `roofline` is for the dominant kernel measured
-with HIP events on the compute stream inside the timed region; `cpu_baseline` is the CPU
-oracle timed on a bounded sample of the same workload on this host.
+and weights resident in HBM.
+
+Default run (`--workload all`): three legs over the same resident weights -- one
+DeepSeek-R1-shaped layer stack of 4 layers laid out as the pipeline workload needs it
+(64 resident + 192 peer-pool experts per layer and two staging buffers):
+  * decode   T=64, layer 0 read in place            -> the headline value and `roofline` (HBM)
+  * prefill  T=8192, the same layer                 -> `roofline_prefill` (FP8 MFMA)
+  * pipeline 4 layers, T=256, layer-ahead prefetch  -> `pipeline` (exposed / hidden copy time)
+Prints ONE JSON line.  `roofline*` are for the dominant kernel of a leg, measured with HIP events
+on the streams the kernels run on inside the timed region; `cpu_baseline` is the CPU oracle
+timed on a bounded sample of the decode workload on this host.
+`--workload decode|prefill|skew|tiny|pipeline` runs one workload alone (profiling, sweeps).
 """
 import argparse
+import hashlib
 import json
 import os
+import re
 import sys
 import time
 
@@ -19,11 +29,6 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 FP8_PEAK_TFLOPS = 5000.0     # MI355X dense FP8 MFMA, published
-# HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs (profiles/:
-# FETCH_SIZE x 2.0 + WRITE_SIZE, calibrated against a 1 GiB copy), keyed by (workload, seed, T); None
-# when this configuration was not profiled.
-PROFILED_TRAFFIC = {("decode", 1, 64): (2325711 * 2 + 1238) * 1024,
-                    ("prefill", 1, 8192): (4361665 * 2 + 152102) * 1024}
 
 
 def parse():
@@ -31,7 +36,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="decode", choices=["decode", "prefill", "skew", "pipeline", "tiny"])
+    ap.add_argument("--workload", default="all", choices=["all", "decode", "prefill", "skew", "pipeline", "tiny"])
+    ap.add_argument("--legs", default="decode,prefill,pipeline",
+                    help="--workload all: which legs to run (decode is always run: it is the headline)")
     ap.add_argument("--T", type=int, default=None, help="override the workload's token count")
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -61,9 +68,34 @@ def parse():
     return ap.parse_args()
 
 
+def profiled_traffic(workload, seed, T, source):
+    """HBM bytes per launch of the dominant kernel from a committed rocprofv3 counter summary, or None.
+
+    A summary under profiles/ may carry a line
+      bench-traffic: workload=<w> seed=<s> T=<t> source=<file under csrc/> sha256=<hex> bytes_per_launch=<n>
+    The figure is used only while the named kernel source still has that hash: a profile of
+    an older kernel says nothing about this run."""
+    pdir, cdir = os.path.join(ROOT, "profiles"), os.path.join(ROOT, "paper_2604_01621_amd", "csrc")
+    try:
+        digest = hashlib.sha256(open(os.path.join(cdir, source), "rb").read()).hexdigest()
+    except OSError:
+        return None
+    pat = re.compile(r"bench-traffic:\s+workload=(\S+)\s+seed=(\d+)\s+T=(\d+)\s+source=(\S+)\s+sha256=([0-9a-f]+)\s+"
+                     r"bytes_per_launch=(\d+)")
+    for name in sorted(os.listdir(pdir)) if os.path.isdir(pdir) else []:
+        if not name.endswith((".md", ".txt")):
+            continue
+        for m in pat.finditer(open(os.path.join(pdir, name)).read()):
+            if (m.group(1), int(m.group(2)), int(m.group(3)), m.group(4), m.group(5)) == \
+                    (workload, seed, T, source, digest):
+                return int(m.group(6))
+    return None
+
+
 def cpu_baseline(cfg, x, logits, bias, w, n_tok):
-    """Time the oracle (as it stands) on the first n_tok tokens of the workload."""
-    import numpy as np
+    """Time the oracle (as it stands) on the first n_tok tokens of the workload.  Returns the
+    baseline record, the oracle's output for those tokens and the same without activation
+    quantisation (the report-only second reading)."""
     from oracle import moe_oracle as mo
     try:
         from threadpoolctl import threadpool_info
@@ -86,28 +118,177 @@ def cpu_baseline(cfg, x, logits, bias, w, n_tok):
     t0 = time.perf_counter()
     ref = mo.moe_forward(xs[:n_tok], lg[:n_tok], bs, ex, spec)
     dt = time.perf_counter() - t0
+    ref_nq = mo.moe_forward(xs[:n_tok], lg[:n_tok], bs, ex, spec, act_quant=False) if w.s13 is not None else None
     return {"value": n_tok / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"first {n_tok} tokens of the workload ({len(need)} experts dequantised), {dt:.1f} s"}, ref
+            "sample": f"first {n_tok} tokens of the workload ({len(need)} experts dequantised), {dt:.1f} s"}, ref, ref_nq
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
-        sys.exit(2)
+def weight_bytes(cfg, binding, inputs):
+    """(bytes of W13 + its scales, bytes of W2 + its scales) of one expert as the kernels read them."""
+    fp8, mx = cfg.w_dtype == inputs.W_FP8, cfg.w_dtype == inputs.W_MXFP4
+    if mx:
+        return (2 * cfg.I * cfg.H // 2 + binding.mx_scale_bytes(2 * cfg.I, cfg.H),
+                cfg.H * cfg.I // 2 + binding.mx_scale_bytes(cfg.H, cfg.I))
+    el = 1 if fp8 else 2
+    return (2 * cfg.I * cfg.H * el + (4 * (2 * cfg.I // 128) * (cfg.H // 128) if fp8 else 0),
+            cfg.H * cfg.I * el + (4 * (cfg.H // 128) * (cfg.I // 128) if fp8 else 0))
+
+
+def time_layer(ctx, cfg, x, logits, bias, table, steps, warmup, calib_copy_mib=0):
+    """W warm-up calls, then K timed dwdp_moe_forward calls between device synchronisations."""
+    import torch
+    y = torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device=x.device)
+    for _ in range(warmup):
+        ctx.dwdp_moe_forward(0, x, logits, bias, table, y)
+    torch.cuda.synchronize()
+    ctx.dwdp_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        ctx.dwdp_moe_forward(0, x, logits, bias, table, y)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    stage_ms, n_calls = ctx.dwdp_profile_read()
+    ctx.dwdp_profile_enable(False)
+    if calib_copy_mib > 0:
+        src = torch.ones(calib_copy_mib << 20, dtype=torch.uint8, device=x.device)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    off = ctx.workspace("offsets", (cfg.E + 1 + cfg.has_shared,), torch.int32).cpu().numpy()
+    return {"y": y, "ms_per_step": dt / steps * 1e3, "stage_ms": {k: v / max(n_calls, 1) for k, v in stage_ms.items()},
+            "counts": off[1:] - off[:-1], "steps": steps, "warmup": warmup}
+
+
+def layer_rooflines(cfg, leg, b13, b2, smr, quantised):
+    """Roofline entries of the two grouped-GEMM stages of one leg.
+
+    The kernel family named is the one that does most of the stage's work, by rows: the
+    LDS-tiled family when it serves at least half of the (token, expert) rows, else the
+    weight-streaming family.  A stage whose tiled experts average 128 rows or more is priced
+    against the FP8 MFMA peak (useful FLOPs, padding not counted), otherwise against HBM
+    (every listed expert's weights read once)."""
+    counts, st = leg["counts"], leg["stage_ms"]
+    if not quantised or cfg.T <= smr:
+        smr = 1 << 30
+    streamed = (counts > 0) & (counts <= smr)
+    tiled = counts > smr
+    n_stream, n_tile = int(streamed.sum()), int(tiled.sum())
+    rows_stream, rows_tile = int(counts[streamed].sum()), int(counts[tiled].sum())
+    fused = st.get("gemm2_tile", 0.0) == 0.0 and st.get("gemm1_tile", 0.0) > 0.0
+
+    def one(stage_stream, stage_tile, bytes_per_expert, flops_per_row, label):
+        use_tile = rows_tile >= rows_stream and n_tile > 0
+        t = st.get(stage_tile, 0.0) if use_tile else st[stage_stream]
+        n_exp = n_tile if use_tile else n_stream
+        kern = ("LDS-tiled " if use_tile else "weight-streaming ") + label
+        if use_tile and rows_tile / max(n_tile, 1) >= 128:
+            ach = rows_tile * flops_per_row / (t * 1e-3) / 1e12
+            hbm = n_tile * bytes_per_expert / (t * 1e-3) / 1e9
+            return {"bound": "mfma", "kernel": kern, "achieved": ach, "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": ach / FP8_PEAK_TFLOPS, "traffic": None,
+                    "algorithmic_flops_per_launch": rows_tile * flops_per_row, "avg_launch_ms": t,
+                    "hbm_read_once_gbs": hbm, "hbm_frac": hbm / HBM_PEAK_GBS}
+        ach = n_exp * bytes_per_expert / (t * 1e-3) / 1e9
+        return {"bound": "hbm", "kernel": kern, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": ach / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_launch": n_exp * bytes_per_expert,
+                "experts_in_launch": n_exp, "avg_launch_ms": t}
+
+    if fused and rows_tile >= rows_stream:
+        # one launch computes both GEMMs of the tiled experts
+        r1 = one("gemm1", "gemm1_tile", b13 + b2, 3 * 2 * cfg.I * cfg.H,
+                 "GEMM-1 (gate/up + SwiGLU) and GEMM-2 (down), one persistent launch")
+        r2 = None
+    else:
+        r1 = one("gemm1", "gemm1_tile", b13, 2 * 2 * cfg.I * cfg.H, "GEMM-1 (gate/up + SwiGLU)")
+        r2 = one("gemm2", "gemm2_tile", b2, 2 * cfg.I * cfg.H, "GEMM-2 (down)")
+    return r1, r2, {"experts_streamed": n_stream, "experts_tiled": n_tile, "rows_streamed": rows_stream,
+                    "rows_tiled": rows_tile}
+
+
+def leg_summary(cfg, leg, b13, b2):
+    counts = leg["counts"]
+    active = int((counts > 0).sum())
+    return {"T": cfg.T, "ms_per_step": leg["ms_per_step"], "tokens_per_s": cfg.T / (leg["ms_per_step"] * 1e-3),
+            "steps": leg["steps"], "warmup": leg["warmup"], "active_expert_slots": active,
+            "token_expert_pairs": int(counts.sum()), "stage_ms": leg["stage_ms"],
+            "layer_weight_gbs": active * (b13 + b2) / (leg["ms_per_step"] * 1e-3) / 1e9}
+
+
+def run_all(args):
+    """The default run: decode, prefill and pipeline legs over one set of resident weights."""
+    import torch
+    import bench_pipeline
+    from paper_2604_01621_amd import binding, inputs
+    dev = torch.device("cuda:0")
+    legs = set(args.legs.split(",")) | {"decode"}
+    T_max = 8192 if "prefill" in legs else 256
+    rig = bench_pipeline.PipelineRig(args.seed, T_max=T_max, copy_engine=args.copy_engine, copy_wgs=args.copy_wgs,
+                                     slice_bytes=args.slice_mib << 20, keep_logical_layer0=not args.no_cpu_baseline,
+                                     dev=dev)
+    ctx = rig.ctx
+    if args.stream_max_rows is not None:
+        ctx.dwdp_set_stream_max_rows(args.stream_max_rows)
+    smr = args.stream_max_rows if args.stream_max_rows is not None else binding.DEFAULT_STREAM_MAX_ROWS
+    # layer 0 with its 192 non-resident experts read in place from the peer pool: every expert resident
+    table = rig.layers.all_resident_table(0, dev)
+
+    cfg_d, x_d, lg_d, b_d = inputs.make_layer_inputs("decode", args.seed, device=dev)
+    b13, b2 = weight_bytes(cfg_d, binding, inputs)
+    leg_d = time_layer(ctx, cfg_d, x_d, lg_d, b_d, table, args.steps, args.warmup, args.calib_copy_mib)
+    roof, roof2, fam = layer_rooflines(cfg_d, leg_d, b13, b2, smr, True)
+    roof["traffic"] = profiled_traffic("decode", args.seed, cfg_d.T, "gemm_stream.hip")
+    dsum = leg_summary(cfg_d, leg_d, b13, b2)
+    out = {
+        "metric": "moe_layer_tokens_per_s", "value": dsum["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": leg_d["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8_e4m3", "data": "synthetic",
+        "config": {"workload": "decode: DeepSeek-R1-shaped MoE layer", "T": cfg_d.T, "H": cfg_d.H, "I": cfg_d.I,
+                   "E": cfg_d.E, "K": cfg_d.K, "shared_experts": cfg_d.has_shared,
+                   "active_expert_slots": dsum["active_expert_slots"], "token_expert_pairs": dsum["token_expert_pairs"],
+                   "weights": "FP8 e4m3 + fp32 128x128 block scales, all resident",
+                   "other_legs": "prefill T=8192 on the same layer (roofline_prefill); 4-layer prefetch pipeline "
+                                 "T=256, 64 resident + 192 staged experts per layer (pipeline)"},
+        "roofline": roof, "roofline_gemm2": roof2, "stage_ms": leg_d["stage_ms"], **fam,
+        "layer_weight_gbs": dsum["layer_weight_gbs"],
+    }
+    if "prefill" in legs:
+        cfg_p, x_p, lg_p, b_p = inputs.make_layer_inputs("prefill", args.seed, device=dev)
+        leg_p = time_layer(ctx, cfg_p, x_p, lg_p, b_p, table, max(3, min(args.steps, 10)), max(1, min(args.warmup, 3)))
+        rp, rp2, famp = layer_rooflines(cfg_p, leg_p, b13, b2, smr, True)
+        rp["traffic"] = profiled_traffic("prefill", args.seed, cfg_p.T, "gemm_tile.hip")
+        psum = leg_summary(cfg_p, leg_p, b13, b2)
+        flops = psum["token_expert_pairs"] * inputs.flops_per_pair(cfg_p)
+        out["roofline_prefill"] = rp
+        if rp2 is not None:
+            out["roofline_prefill_gemm2"] = rp2
+        out["prefill"] = {**psum, **famp, "layer_tflops": flops / (leg_p["ms_per_step"] * 1e-3) / 1e12,
+                          "layer_frac_of_fp8_peak": flops / (leg_p["ms_per_step"] * 1e-3) / 1e12 / FP8_PEAK_TFLOPS}
+        del leg_p, x_p, lg_p
+    if "pipeline" in legs:
+        out["pipeline"] = rig.measure(max(2, min(args.steps, 5)), max(1, min(args.warmup, 2)))
+    if not args.no_cpu_baseline:
+        from oracle import moe_oracle as mo
+        n_tok = min(args.cpu_sample_tokens, cfg_d.T)
+        cb, ref, ref_nq = cpu_baseline(cfg_d, x_d, lg_d, b_d, rig.layers.logical[0], n_tok)
+        out["cpu_baseline"] = cb
+        got = leg_d["y"][:n_tok].float().cpu().numpy()
+        out["sample_max_rel_err"] = mo.error_metrics(got, ref)[0]
+        out["sample_max_rel_err_per_token"] = mo.error_metric_rows(got, ref)
+        # report only: distance to the same layer without activation quantisation (the other reading of
+        # "bf16 activations"); the parity reference is the one above
+        out["sample_err_vs_unquantised_activations"] = {"gpu": mo.error_metrics(got, ref_nq)[0],
+                                                        "oracle": mo.error_metrics(ref, ref_nq)[0]}
+    rig.close()
+    return out
+
+
+def run_single(args):
     import torch
     from paper_2604_01621_amd import binding, inputs
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-
-    if args.workload == "pipeline":
-        from paper_2604_01621_amd import pipeline_bench
-        out = pipeline_bench.run_pullers(args) if args.pullers > 1 else pipeline_bench.run(args)
-        print(json.dumps(out))
-        return
-
     cfg, x, logits, bias = inputs.make_layer_inputs(args.workload, args.seed, device=dev, T=args.T)
     if args.weights == "mxfp4" and cfg.w_dtype == inputs.W_FP8:
         import dataclasses
@@ -119,104 +300,63 @@ def main():
         ctx.dwdp_set_stream_max_rows(args.stream_max_rows)
     wp = ctx.pack_experts(w)          # one-off weight preparation, outside the timed region
     table = binding.expert_table(wp)
-    y = torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device=dev)
     torch.cuda.synchronize()
-
-    for _ in range(args.warmup):
-        ctx.dwdp_moe_forward(0, x, logits, bias, table, y)
-    torch.cuda.synchronize()
-    ctx.dwdp_profile_enable(True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        ctx.dwdp_moe_forward(0, x, logits, bias, table, y)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    stage_ms, n_calls = ctx.dwdp_profile_read()
-    ctx.dwdp_profile_enable(False)
-    stage_ms = {k: v / max(n_calls, 1) for k, v in stage_ms.items()}
-
-    if args.calib_copy_mib > 0:
-        src = torch.ones(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
-    n_off = cfg.E + 1 + cfg.has_shared
-    off = ctx.workspace("offsets", (n_off,), torch.int32).cpu().numpy()
-    counts = off[1:] - off[:-1]
-    active = int((counts > 0).sum())
-    pairs = int(counts.sum())
-    ms_per_step = dt / args.steps * 1e3
-
+    leg = time_layer(ctx, cfg, x, logits, bias, table, args.steps, args.warmup, args.calib_copy_mib)
     fp8 = cfg.w_dtype == inputs.W_FP8
     mx = cfg.w_dtype == inputs.W_MXFP4
-    el = 1 if fp8 else 2
-    if mx:      # packed codes + packed scales as the kernels read them
-        b13 = 2 * cfg.I * cfg.H // 2 + binding.mx_scale_bytes(2 * cfg.I, cfg.H)
-        b2 = cfg.H * cfg.I // 2 + binding.mx_scale_bytes(cfg.H, cfg.I)
-    else:
-        b13 = 2 * cfg.I * cfg.H * el + (4 * (2 * cfg.I // 128) * (cfg.H // 128) if fp8 else 0)
-        b2 = cfg.H * cfg.I * el + (4 * (cfg.H // 128) * (cfg.I // 128) if fp8 else 0)
-    # which kernel family serves which expert (the library's default threshold: 16 rows)
-    smr = args.stream_max_rows if args.stream_max_rows is not None else 16
-    if not (fp8 or mx) or cfg.T <= smr:
-        smr = 1 << 30
-    n_stream = int(((counts > 0) & (counts <= smr)).sum())
-    n_tile = int((counts > smr).sum())
-    rows_tile = int(counts[counts > smr].sum())
-
-    def roofline(stage_stream, stage_tile, bytes_per_expert, flops_per_row, label):
-        """Roofline entry for the kernel family that does most of one GEMM stage's work."""
-        t_s, t_t = stage_ms[stage_stream], stage_ms.get(stage_tile, 0.0)
-        tile = n_tile > n_stream          # the family that serves more experts does more of the work
-        t = t_t if tile else t_s
-        n_exp = n_tile if tile else n_stream
-        kern = ("LDS-tiled " if tile else "weight-streaming ") + label
-        compute_bound = tile and rows_tile / max(n_tile, 1) >= 128
-        if compute_bound:
-            ach = rows_tile * flops_per_row / (t * 1e-3) / 1e12
-            # the same launch against the HBM roofline: every listed expert's weights read once
-            hbm = n_tile * bytes_per_expert / (t * 1e-3) / 1e9
-            return {"bound": "mfma", "kernel": kern, "achieved": ach, "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": ach / FP8_PEAK_TFLOPS, "traffic": None,
-                    "algorithmic_flops_per_launch": rows_tile * flops_per_row, "avg_launch_ms": t,
-                    "hbm_read_once_gbs": hbm, "hbm_frac": hbm / HBM_PEAK_GBS}
-        ach = n_exp * bytes_per_expert / (t * 1e-3) / 1e9
-        return {"bound": "hbm", "kernel": kern, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": ach / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_launch": n_exp * bytes_per_expert,
-                "experts_in_launch": n_exp, "avg_launch_ms": t}
-
-    roof = roofline("gemm1", "gemm1_tile", b13, 2 * 2 * cfg.I * cfg.H, "GEMM-1 (gate/up + SwiGLU)")
-    roof2 = roofline("gemm2", "gemm2_tile", b2, 2 * cfg.I * cfg.H, "GEMM-2 (down)")
-    if args.stream_max_rows is None and not mx:
-        roof["traffic"] = PROFILED_TRAFFIC.get((args.workload, args.seed, cfg.T))
-
+    b13, b2 = weight_bytes(cfg, binding, inputs)
+    smr = args.stream_max_rows if args.stream_max_rows is not None else binding.DEFAULT_STREAM_MAX_ROWS
+    roof, roof2, fam = layer_rooflines(cfg, leg, b13, b2, smr, fp8 or mx)
+    if args.stream_max_rows is None and fp8:
+        roof["traffic"] = profiled_traffic(args.workload, args.seed, cfg.T,
+                                           "gemm_tile.hip" if roof["kernel"].startswith("LDS") else "gemm_stream.hip")
+    s = leg_summary(cfg, leg, b13, b2)
     out = {
-        "metric": "moe_layer_tokens_per_s", "value": cfg.T / (ms_per_step * 1e-3), "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "metric": "moe_layer_tokens_per_s", "value": s["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": leg["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "fp8_e4m3" if fp8 else ("mxfp4 weights x fp8_e4m3 activations" if mx else "bf16"), "data": "synthetic",
         "config": {"workload": f"{args.workload}: DeepSeek-R1-shaped MoE layer" if args.workload != "tiny"
                    else "tiny bf16 MoE layer", "T": cfg.T, "H": cfg.H, "I": cfg.I, "E": cfg.E, "K": cfg.K,
-                   "shared_experts": cfg.has_shared, "active_expert_slots": active, "token_expert_pairs": pairs,
+                   "shared_experts": cfg.has_shared, "active_expert_slots": s["active_expert_slots"],
+                   "token_expert_pairs": s["token_expert_pairs"],
                    "weights": "FP8 e4m3 + fp32 128x128 block scales, all resident" if fp8 else
                    ("MXFP4 (E2M1 + E8M0 per 32), all resident" if mx else "bf16, all resident")},
-        "roofline": roof, "roofline_gemm2": roof2, "stage_ms": stage_ms,
-        "experts_streamed": n_stream, "experts_tiled": n_tile,
-        "layer_weight_gbs": active * (b13 + b2) / (ms_per_step * 1e-3) / 1e9,
+        "roofline": roof, "roofline_gemm2": roof2, "stage_ms": leg["stage_ms"], **fam,
+        "layer_weight_gbs": s["layer_weight_gbs"],
+        "layer_tflops": s["token_expert_pairs"] * inputs.flops_per_pair(cfg) / (leg["ms_per_step"] * 1e-3) / 1e12,
     }
     if not args.no_cpu_baseline:
-        n_tok = min(args.cpu_sample_tokens, cfg.T)
-        cb, ref = cpu_baseline(cfg, x, logits, bias, w, n_tok)
-        out["cpu_baseline"] = cb
         from oracle import moe_oracle as mo
-        err, l2 = mo.error_metrics(y[:n_tok].float().cpu().numpy(), ref)
-        out["sample_max_rel_err"] = err
-    print(json.dumps(out))
+        n_tok = min(args.cpu_sample_tokens, cfg.T)
+        cb, ref, ref_nq = cpu_baseline(cfg, x, logits, bias, w, n_tok)
+        out["cpu_baseline"] = cb
+        got = leg["y"][:n_tok].float().cpu().numpy()
+        out["sample_max_rel_err"] = mo.error_metrics(got, ref)[0]
+        out["sample_max_rel_err_per_token"] = mo.error_metric_rows(got, ref)
+        if ref_nq is not None:
+            out["sample_err_vs_unquantised_activations"] = {"gpu": mo.error_metrics(got, ref_nq)[0],
+                                                            "oracle": mo.error_metrics(ref, ref_nq)[0]}
     ctx.close()
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(torch.device("cuda:0"))
+    if args.workload == "pipeline":
+        import bench_pipeline
+        out = bench_pipeline.run_pullers(args) if args.pullers > 1 else bench_pipeline.run(args)
+    elif args.workload == "all":
+        out = run_all(args)
+    else:
+        out = run_single(args)
+    print(json.dumps(out))
 
 
 if __name__ == "__main__":

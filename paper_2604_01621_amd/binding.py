@@ -19,6 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdwdp.so")
 
 OK, EINVAL, ESHAPE, ENOMEM, EHIP, ESTATE = range(6)
+DEFAULT_STREAM_MAX_ROWS = 16     # the library's default kernel-selection threshold (dwdp_set_stream_max_rows)
 STAGES = ("route", "permute", "quant", "gemm1", "gemm2", "combine", "gemm1_tile", "gemm2_tile")
 WS = {"topk_ids": 0, "topk_w": 1, "offsets": 2, "perm": 3, "inv_perm": 4, "xq": 5, "xs": 6, "hq": 7, "hs": 8, "yp": 9}
 
