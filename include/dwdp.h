@@ -177,14 +177,35 @@ dwdp_status dwdp_prefetch_layer(dwdp_ctx* ctx, int32_t layer, const void* const*
                                 const size_t* bytes, int32_t n_peers, int32_t n_params, size_t slice_bytes);
 
 /*
- * Kernel selection of the FP8 / MXFP4 grouped GEMM.  Experts with 1..max_rows sorted rows are
- * computed by the weight-streaming kernels (weights straight to registers, 16 token rows per
- * pass over the weights), experts with more rows by the LDS-tiled kernels (288-token tiles,
- * weights read once per tile).  Default 16.  0 sends every
- * expert to the tiled kernels; a value >= T_max sends every expert to the streaming
- * kernels.  Results are the same function either way (accumulation order differs).
+ * Kernel selection of the FP8 / MXFP4 grouped GEMM by an expert's number of sorted rows m.
+ *   1 <= m <= min(max_rows, 16): weight-streaming kernels, one 16-token tile per pass over the weights;
+ *   16 < m <= max_rows (FP8 weights): the same streams with four token tiles per pass, in row
+ *     groups of 64 (weights read once per 64 rows; workgroups small enough to share a compute
+ *     unit with other kernels); with MXFP4 weights these experts are walked 16 rows at a time;
+ *   m > max_rows: LDS-tiled kernels (288-token tiles, weights read once per tile, workgroups
+ *     that each fill a compute unit) -- unless fewer than about half a chip's worth of tiles
+ *     come together in a call (decided on the device) or the experts of the call average fewer
+ *     than 16 rows (decided on the host): such outliers join the row groups (FP8 weights).
+ * Default: 64 with FP8 weights, 16 with MXFP4 weights.  0 sends every expert to the tiled
+ * kernels; a value >= T_max sends every expert to the streaming kernels.  Results are the same
+ * function either way (accumulation order differs).
  */
 dwdp_status dwdp_set_stream_max_rows(dwdp_ctx* ctx, int32_t max_rows);
+
+/*
+ * How the work items (M tile of up to 288 rows x weight panel) of the LDS-tiled kernels are handed
+ * to workgroups.  Same results in every mode, bit for bit.
+ *   DWDP_TILE_PER_ITEM (default): one workgroup per item, one launch per GEMM; finished
+ *     workgroups return their compute unit, so the weight-streaming chain that runs beside the
+ *     tiled one gets units as soon as fewer items are left than the chip has units.
+ *   DWDP_TILE_PERSISTENT: per GEMM one launch of at most one workgroup per compute unit; the
+ *     workgroups take items by atomic tickets (one queue per XCD, idle dies take others' tickets).
+ *   DWDP_TILE_PERSISTENT_FUSED: ONE such launch computes both grouped GEMMs of the tiled experts; a
+ *     down-projection item waits on a device-side counter for the gate/up items of its rows
+ *     (bounded wait; DWDP_WS_SCHED word 16 reports a wait that gave up).
+ */
+enum { DWDP_TILE_PER_ITEM = 0, DWDP_TILE_PERSISTENT = 1, DWDP_TILE_PERSISTENT_FUSED = 2 };
+dwdp_status dwdp_set_tile_schedule(dwdp_ctx* ctx, int32_t mode);
 
 /*
  * Weight preparation, done once when weights are loaded (on the owner of every expert,
@@ -276,7 +297,8 @@ dwdp_status dwdp_merge_experts(dwdp_ctx* ctx, int32_t layer, const dwdp_expert_p
  * read into ms_sum[DWDP_N_STAGES] (HOST), stores the number of calls in *n_calls and
  * resets.  At most DWDP_PROFILE_MAX_CALLS calls are kept between reads.
  * With FP8 weights the grouped GEMMs run as two concurrent chains: GEMM1_TILE/GEMM2_TILE are
- * the LDS-tiled kernels on the compute stream, GEMM1/GEMM2 the weight-streaming kernels on an
+ * the LDS-tiled kernels on the compute stream (with DWDP_TILE_PERSISTENT_FUSED, GEMM1_TILE is the
+ * one launch that computes both and GEMM2_TILE is zero), GEMM1/GEMM2 the weight-streaming kernels on an
  * internal stream forked from and joined back into it (on the compute stream when no expert
  * can be tiled); QUANT is the time between the permutation's end and the first GEMM (any wait
  * for prefetched experts).
@@ -329,7 +351,9 @@ enum {
   DWDP_WS_HQ = 7,       /* fp8 (FP8) or fp32 (bf16) [rows,I] */
   DWDP_WS_HS = 8,       /* fp32 [rows,I/128]  (FP8 only)    */
   DWDP_WS_YP = 9,       /* bf16 (FP8) or fp32 (bf16) [rows,H] */
-  DWDP_N_WS = 10
+  DWDP_WS_SCHED = 10,   /* int32 [32 + tiles]: scheduler words of the persistent tiled GEMM; [16] != 0
+                           after a call means a bounded device-side wait gave up (results invalid)  */
+  DWDP_N_WS = 11
 };
 void* dwdp_workspace_ptr(dwdp_ctx* ctx, int32_t which);
 

@@ -19,9 +19,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdwdp.so")
 
 OK, EINVAL, ESHAPE, ENOMEM, EHIP, ESTATE = range(6)
-DEFAULT_STREAM_MAX_ROWS = 16     # the library's default kernel-selection threshold (dwdp_set_stream_max_rows)
+DEFAULT_STREAM_MAX_ROWS = 64     # the library's default kernel-selection threshold (dwdp_set_stream_max_rows)
 STAGES = ("route", "permute", "quant", "gemm1", "gemm2", "combine", "gemm1_tile", "gemm2_tile")
-WS = {"topk_ids": 0, "topk_w": 1, "offsets": 2, "perm": 3, "inv_perm": 4, "xq": 5, "xs": 6, "hq": 7, "hs": 8, "yp": 9}
+WS = {"topk_ids": 0, "topk_w": 1, "offsets": 2, "perm": 3, "inv_perm": 4, "xq": 5, "xs": 6, "hq": 7, "hs": 8, "yp": 9, "sched": 10}
 
 
 class dwdp_config(C.Structure):
@@ -63,6 +63,7 @@ def _load() -> C.CDLL:
     lib.dwdp_merge_experts.argtypes = [vp, i32, C.POINTER(dwdp_expert_ptrs), i32, vp, vp, vp, vp,
                                        C.POINTER(dwdp_expert_ptrs)]
     lib.dwdp_set_stream_max_rows.argtypes = [vp, i32]
+    lib.dwdp_set_tile_schedule.argtypes = [vp, i32]
     lib.dwdp_set_copy_engine.argtypes = [vp, i32, i32]
     lib.dwdp_pack_fp8_weight.argtypes = [vp, vp, vp, C.c_int64, C.c_int64]
     lib.dwdp_pack_mxfp4_weight.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int64]
@@ -213,6 +214,10 @@ class Context:
 
     def dwdp_set_stream_max_rows(self, max_rows: int):
         self._check(lib.dwdp_set_stream_max_rows(self.h, max_rows))
+
+    def dwdp_set_tile_schedule(self, mode: int):
+        """0: one workgroup per item; 1: persistent per GEMM; 2: persistent, both GEMMs in one launch."""
+        self._check(lib.dwdp_set_tile_schedule(self.h, mode))
 
     def dwdp_pack_fp8_weight(self, src: torch.Tensor, dst: torch.Tensor):
         """src uint8 [..., rows, cols] row-major matrices -> dst (same shape) tile-major, matrix by matrix."""

@@ -26,11 +26,18 @@ struct dwdp_ctx {
   void* ws[DWDP_N_WS] = {};
   int32_t* chunk_counts = nullptr;
   // LDS-tiled GEMM schedule (FP8): experts with more than stream_max_rows rows
-  int stream_max_rows = 16;
+  int stream_max_rows = -1;  // -1: the default for the weight format (see dwdp_set_stream_max_rows)
+  int32_t* mid_expert = nullptr;  // row groups of the experts with 17 .. stream_max_rows rows
+  int32_t* mid_row0 = nullptr;
+  int32_t* n_mid = nullptr;
+  int mid_cap = 0;
   int32_t* mt_expert = nullptr;
   int32_t* mt_row0 = nullptr;
   int32_t* n_mtiles = nullptr;
+  int32_t* sched_sync = nullptr;  // ticket queues, error word and per-tile counters of the persistent tiled GEMM
   int mt_cap = 0;
+  int n_cus = 256;
+  int tile_schedule = DWDP_TILE_PER_ITEM;
   // prefetch engine: 0 = one hipMemcpyAsync per plan entry, 1 = one copy-plan kernel launch
   int copy_mode = 0;
   int copy_wgs = 256;
@@ -145,6 +152,7 @@ extern "C" dwdp_status dwdp_create(const dwdp_config* cfg, void* compute_stream,
   bytes[DWDP_WS_HQ] = c->rows_max * I * (fp8 ? 1 : 4);
   bytes[DWDP_WS_HS] = fp8 ? c->rows_max * (I / 128) * 4 + 16 : 0;
   bytes[DWDP_WS_YP] = c->rows_max * H * (fp8 ? 2 : 4);
+  bytes[DWDP_WS_SCHED] = 0;  // allocated below with the tile list (sched_sync)
   hipError_t e = hipGetDevice(&c->device);
   for (int i = 0; i < DWDP_N_WS && e == hipSuccess; i++)
     if (bytes[i]) e = hipMalloc(&c->ws[i], bytes[i]);
@@ -155,6 +163,14 @@ extern "C" dwdp_status dwdp_create(const dwdp_config* cfg, void* compute_stream,
   if (e == hipSuccess) e = hipMalloc((void**)&c->mt_expert, (size_t)c->mt_cap * 4);
   if (e == hipSuccess) e = hipMalloc((void**)&c->mt_row0, (size_t)c->mt_cap * 4);
   if (e == hipSuccess) e = hipMalloc((void**)&c->n_mtiles, 4);
+  c->mid_cap = mid_groups_cap((int)c->rows_max, c->n_slots, 17);
+  if (e == hipSuccess) e = hipMalloc((void**)&c->mid_expert, (size_t)c->mid_cap * 4);
+  if (e == hipSuccess) e = hipMalloc((void**)&c->mid_row0, (size_t)c->mid_cap * 4);
+  if (e == hipSuccess) e = hipMalloc((void**)&c->n_mid, 4);
+  if (e == hipSuccess) e = hipMalloc((void**)&c->sched_sync, (size_t)tile_sync_words(c->mt_cap) * 4);
+  if (e == hipSuccess) e = hipMemset(c->sched_sync, 0, (size_t)tile_sync_words(c->mt_cap) * 4);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, c->device);
+  if (e == hipSuccess && c->n_cus < 8) c->n_cus = 8;
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->copy, hipStreamNonBlocking);
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&c->fork_ev, hipEventDisableTiming);
@@ -183,6 +199,10 @@ extern "C" void dwdp_destroy(dwdp_ctx* c) {
   if (c->mt_expert) (void)hipFree(c->mt_expert);
   if (c->mt_row0) (void)hipFree(c->mt_row0);
   if (c->n_mtiles) (void)hipFree(c->n_mtiles);
+  if (c->sched_sync) (void)hipFree(c->sched_sync);
+  if (c->mid_expert) (void)hipFree(c->mid_expert);
+  if (c->mid_row0) (void)hipFree(c->mid_row0);
+  if (c->n_mid) (void)hipFree(c->n_mid);
   for (auto& pc : c->plan_cache) {
     if (pc.units) (void)hipFree(pc.units);
     if (pc.units_host) (void)hipHostFree(pc.units_host);
@@ -353,11 +373,38 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
   // Experts with 1..smr rows stream their weights; the others go through the LDS-tiled kernel
   // (FP8 and MXFP4 weights).
   const int rows = T * c.K + (c.has_shared ? T : 0);
-  const int smr = ctx->stream_max_rows;
-  const bool use_tile = fp8 && T > smr;  // an expert holds at most T rows
+  // Default threshold: 64 rows with FP8 weights (17 .. 64 rows go to the multi-tile streaming
+  // items), 16 with MXFP4 weights (no multi-tile items there: larger experts go to the tiled kernels).
+  const int smr = ctx->stream_max_rows >= 0 ? ctx->stream_max_rows : (mx ? 16 : 64);
   const bool use_stream = smr > 0;
-  TileSched ts{ctx->mt_expert, ctx->mt_row0, ctx->n_mtiles, 0};
-  if (use_tile) ts.n_mt_max = tile_mtiles_cap(rows, ctx->n_slots, smr);
+  const bool use_mid = fp8 && !mx && smr > 16 && T > 16;
+  // The tiled kernels are launched when an expert can have more than smr rows (it holds at most
+  // T) -- and, when the row-group items exist as the alternative, only if the experts average at
+  // least 16 rows: below that a tiled expert is a rare outlier (the shared expert, a hot routed
+  // one), which the device-side rule of the list builder would send to the row groups anyway,
+  // and the launch is skipped because even its surplus workgroups each need a whole compute unit
+  // to start and exit (next to a prefetch copy that occupies every unit they wait for it to end).
+  const bool use_tile = fp8 && T > smr && (!use_mid || (long)rows >= 16L * ctx->n_slots);
+  TileSched ts{};
+  if (use_tile) {
+    ts.mt_expert = ctx->mt_expert;
+    ts.mt_row0 = ctx->mt_row0;
+    ts.n_mtiles = ctx->n_mtiles;
+    ts.sync = ctx->sched_sync;
+    ts.n_mt_max = tile_mtiles_cap(rows, ctx->n_slots, smr);
+    ts.sync_words = tile_sync_words(ts.n_mt_max);
+    // fewer tiled GEMM-1 items than half the compute units: not worth whole-unit workgroups
+    const int p1 = c.I / 128;
+    ts.min_tiles = use_mid ? (ctx->n_cus / 2 + p1 - 1) / p1 : 0;
+  }
+  if (use_mid) {
+    ts.mid_expert = ctx->mid_expert;
+    ts.mid_row0 = ctx->mid_row0;
+    ts.n_mid = ctx->n_mid;
+    ts.mid_min_rows = 17;
+    // groups of the experts with 17 .. min(smr, T) rows
+    ts.mid_cap = mid_groups_cap(rows, ctx->n_slots, 17);
+  }
   // Two launches prepare the GEMMs: routing with the (independent) activation quantisation
   // riding along as extra workgroups, and the permutation, whose last single-workgroup step
   // also lists the M tiles of the tiled experts.
@@ -369,7 +416,8 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
   else
     launch_route(logits, rbias, T, route_params(c), ids, tw, s);
   if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_PERMUTE), s));
-  launch_permute(ids, T, c.E, c.K, c.has_shared, ctx->chunk_counts, off, perm, inv, use_tile ? &ts : nullptr, smr, s);
+  launch_permute(ids, T, c.E, c.K, c.has_shared, ctx->chunk_counts, off, perm, inv,
+                 (use_tile || use_mid) ? &ts : nullptr, smr, s);
   if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_QUANT), s));
   // Only the grouped GEMMs read expert weights: the wait for the staged experts goes here.
   if (consume) HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->staged_ev[layer], 0));
@@ -393,14 +441,14 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
         launch_gemm1_mx(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
                         (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], sc);
       else
-        launch_gemm1_fp8(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
+        launch_gemm1_fp8(ga, smr, ts, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
                          (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], sc);
       if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, DWDP_STAGE_GEMM2), sc));
       if (mx)
         launch_gemm2_mx(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
                         ctx->ws[DWDP_WS_YP], sc);
       else
-        launch_gemm2_fp8(ga, smr, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
+        launch_gemm2_fp8(ga, smr, ts, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
                          ctx->ws[DWDP_WS_YP], sc);
       if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfStreamEnd), sc));
       if (two) HIP_TRY(ctx, hipEventRecord(ctx->join_ev, ctx->aux));
@@ -410,12 +458,18 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
       HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfStreamEnd), s));
     }
     if (use_tile) {
+      // one launch per GEMM (GEMM1_TILE and GEMM2_TILE timed separately), or with the fused
+      // persistent schedule one launch for both (GEMM1_TILE is the whole launch, GEMM2_TILE zero)
+      const uint8_t* xq = (const uint8_t*)ctx->ws[DWDP_WS_XQ];
+      const float* xs = (const float*)ctx->ws[DWDP_WS_XS];
+      uint8_t* hq = (uint8_t*)ctx->ws[DWDP_WS_HQ];
+      float* hs = (float*)ctx->ws[DWDP_WS_HS];
+      const int sched = ctx->tile_schedule == DWDP_TILE_PER_ITEM ? 0 : 1;
+      const bool fused = ctx->tile_schedule == DWDP_TILE_PERSISTENT_FUSED;
       if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfMain + 1), s));
-      launch_gemm1_fp8_tile(ga, ts, mx, (const uint8_t*)ctx->ws[DWDP_WS_XQ], (const float*)ctx->ws[DWDP_WS_XS],
-                            (uint8_t*)ctx->ws[DWDP_WS_HQ], (float*)ctx->ws[DWDP_WS_HS], s);
+      launch_gemm_fp8_tile(ga, ts, mx, sched, fused ? 3 : 1, xq, xs, hq, hs, ctx->ws[DWDP_WS_YP], ctx->n_cus, s);
       if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfMain + 2), s));
-      launch_gemm2_fp8_tile(ga, ts, mx, (const uint8_t*)ctx->ws[DWDP_WS_HQ], (const float*)ctx->ws[DWDP_WS_HS],
-                            ctx->ws[DWDP_WS_YP], s);
+      if (!fused) launch_gemm_fp8_tile(ga, ts, mx, sched, 2, xq, xs, hq, hs, ctx->ws[DWDP_WS_YP], ctx->n_cus, s);
       if (prof) HIP_TRY(ctx, hipEventRecord(prof_event(ctx, kProfMain + 3), s));
     }
     if (two) {
@@ -675,6 +729,14 @@ extern "C" dwdp_status dwdp_set_stream_max_rows(dwdp_ctx* ctx, int32_t max_rows)
   return DWDP_OK;
 }
 
+extern "C" dwdp_status dwdp_set_tile_schedule(dwdp_ctx* ctx, int32_t mode) {
+  if (!ctx) return DWDP_EINVAL;
+  if (mode != DWDP_TILE_PER_ITEM && mode != DWDP_TILE_PERSISTENT && mode != DWDP_TILE_PERSISTENT_FUSED)
+    return fail(ctx, DWDP_EINVAL, "dwdp_set_tile_schedule: unknown mode %d", mode);
+  ctx->tile_schedule = mode;
+  return DWDP_OK;
+}
+
 extern "C" dwdp_status dwdp_pack_fp8_weight(dwdp_ctx* ctx, const void* src, void* dst, int64_t rows, int64_t cols) {
   if (!ctx) return DWDP_EINVAL;
   if (rows < 0 || cols < 0) return fail(ctx, DWDP_EINVAL, "dwdp_pack_fp8_weight: negative size");
@@ -778,6 +840,7 @@ extern "C" dwdp_status dwdp_timeline_read(dwdp_ctx* ctx, int32_t* kind, int32_t*
 
 extern "C" void* dwdp_workspace_ptr(dwdp_ctx* ctx, int32_t which) {
   if (!ctx || which < 0 || which >= DWDP_N_WS) return nullptr;
+  if (which == DWDP_WS_SCHED) return ctx->sched_sync;
   return ctx->ws[which];
 }
 

@@ -40,10 +40,29 @@ struct TileSched {
   int32_t* mt_expert;  // [n_mt_max] expert slot of the tile
   int32_t* mt_row0;    // [n_mt_max] first sorted row
   int32_t* n_mtiles;   // [1] tiles listed
-  int n_mt_max;        // host-side upper bound used to size the grid
+  int32_t* sync;       // [tile_sync_words(capacity)] ticket queues, error word, per-tile counters of the
+                       // persistent tiled GEMM; zeroed by the kernel that builds the list
+  int n_mt_max;        // host-side upper bound of the tiles listed by this call
+  int sync_words;      // words of `sync` to zero
+  int min_tiles;       // fewer M tiles than this (device-side count): none is listed, and when the row-group
+                       // list is built those experts go there instead (see build_work_lists_block)
+  // Row groups (up to kMidRows sorted rows of one expert) of the experts with mid_min_rows ..
+  // stream_max_rows rows, for the multi-tile weight-streaming kernels; mid_expert == nullptr: not listed.
+  int32_t* mid_expert;  // [mid_cap]
+  int32_t* mid_row0;    // [mid_cap] first sorted row of the group
+  int32_t* n_mid;       // [1]
+  int mid_cap;
+  int mid_min_rows;
 };
+constexpr int kMidRows = 64;        // rows of one group of the multi-tile streaming kernels (4 tiles of 16)
+// Upper bound of listed row groups for `rows` sorted rows over n_slots experts.
+int mid_groups_cap(int rows, int n_slots, int mid_min_rows);
+constexpr int kTileSyncError = 16;  // sync[16]: a bounded wait of the tiled GEMM gave up
+constexpr int kTileSyncDone = 32;   // sync[32 + m]: finished GEMM-1 items of M tile m
 // Upper bound of listed tiles when experts with more than stream_max_rows rows are listed.
 int tile_mtiles_cap(int rows, int n_slots, int stream_max_rows);
+// Words of TileSched::sync for a list of at most mt_cap tiles.
+int tile_sync_words(int mt_cap);
 
 // chunk_counts: int32 [n_chunks * E] scratch.  With `list` non-null the single workgroup that
 // finishes the offsets also lists the M tiles of all experts with more than stream_max_rows
@@ -80,16 +99,21 @@ void launch_pack_fp8_tiles(const void* src, void* dst, long rows, int cols, hipS
 
 // FP8 (weights tile-major): h = quant(silu(Xq Wg^T) * (Xq Wu^T)); hq fp8 [rows,I], hs fp32 [rows,I/128]
 // Streaming kernels: experts with 1..max_rows rows.  LDS-tiled kernels: the experts in the tile list.
-void launch_gemm1_fp8(const GemmArgs& a, int max_rows, const uint8_t* xq, const float* xs, uint8_t* hq, float* hs,
-                      hipStream_t stream);
-// mxfp4: the listed experts' weights are MXFP4 (launch_pack_mxfp4 layouts) instead of FP8
-void launch_gemm1_fp8_tile(const GemmArgs& a, const TileSched& ts, bool mxfp4, const uint8_t* xq, const float* xs,
-                           uint8_t* hq, float* hs, hipStream_t stream);
+// `ts` carries the row-group list of the experts with 17 .. max_rows rows (ts.mid_expert may be
+// nullptr: then experts with more than 16 rows are walked 16 rows at a time, re-reading the weights).
+void launch_gemm1_fp8(const GemmArgs& a, int max_rows, const TileSched& ts, const uint8_t* xq, const float* xs,
+                      uint8_t* hq, float* hs, hipStream_t stream);
+// The LDS-tiled pair for the experts of the tile list.  schedule 0: one workgroup per (M tile,
+// panel) item, one launch per GEMM (phase_mask 1, then 2).  schedule 1: persistent launches of at
+// most n_cus workgroups that take items by atomic tickets -- phase_mask 3: GEMM-1 then GEMM-2 items
+// in one launch with device-side dependency counters; 1 or 2: one GEMM per launch.
+// mxfp4: the listed experts' weights are MXFP4 (launch_pack_mxfp4 layouts) instead of FP8.
+void launch_gemm_fp8_tile(const GemmArgs& a, const TileSched& ts, bool mxfp4, int schedule, int phase_mask,
+                          const uint8_t* xq, const float* xs, uint8_t* hq, float* hs, void* yp, int n_cus,
+                          hipStream_t stream);
 // FP8: yp = Hq W2^T, bf16 [rows,H]
-void launch_gemm2_fp8(const GemmArgs& a, int max_rows, const uint8_t* hq, const float* hs, void* yp,
-                      hipStream_t stream);
-void launch_gemm2_fp8_tile(const GemmArgs& a, const TileSched& ts, bool mxfp4, const uint8_t* hq, const float* hs,
-                           void* yp, hipStream_t stream);
+void launch_gemm2_fp8(const GemmArgs& a, int max_rows, const TileSched& ts, const uint8_t* hq, const float* hs,
+                      void* yp, hipStream_t stream);
 // MXFP4 weights (layouts of launch_pack_mxfp4), FP8 activations: same results as the FP8 pair above
 void launch_gemm1_mx(const GemmArgs& a, int max_rows, const uint8_t* xq, const float* xs, uint8_t* hq, float* hs,
                      hipStream_t stream);
@@ -158,47 +182,80 @@ __device__ __forceinline__ void quant_act_lane(const uint16_t* __restrict__ x, l
   }
 }
 
-// Lists the M tiles (kTileM rows each) of all experts that have more than stream_max_rows rows.
-// Called by ONE workgroup of 1024 threads after it has written offsets[0..n_slots] (global
-// memory; a __syncthreads separates the writes from this call); thread i owns expert slots
-// 2i and 2i+1, an exclusive block scan of the tile counts gives every expert its place in
-// the list.  scan_s: 1024 ints of LDS.
-__device__ __forceinline__ void build_mtile_list_block(const int32_t* offsets, int n_slots, int stream_max_rows,
-                                                       int32_t* __restrict__ mt_expert, int32_t* __restrict__ mt_row0,
-                                                       int32_t* __restrict__ n_mtiles, int cap, int32_t* scan_s) {
+// Work lists of the grouped GEMMs, built by ONE workgroup of 1024 threads after it has written
+// offsets[0..n_slots] (global memory; a __syncthreads separates the writes from this call).
+// Thread i owns expert slots 2i and 2i+1; exclusive block scans give every expert its place.
+//   * M tiles (kTileM rows each) of all experts with more than stream_max_rows rows, for the LDS-tiled GEMM;
+//   * row groups (kMidRows rows each) of all experts with mid_min_rows .. stream_max_rows rows, for
+//     the multi-tile streaming kernels (only when s.mid_expert is set).
+// Also zeroes the scheduler words of the persistent tiled GEMM.  scan_s: 1024 ints of LDS.
+__device__ __forceinline__ void build_work_lists_block(const int32_t* offsets, int n_slots, int stream_max_rows,
+                                                       const TileSched& s, int32_t* scan_s) {
   const int tid = threadIdx.x;
-  int cnt[2], r0[2];
+  // scheduler words of the persistent tiled GEMM (ticket queues, error word, per-tile counters)
+  for (int i = tid; i < s.sync_words; i += 1024) s.sync[i] = 0;
+  int m[2], r0[2];
 #pragma unroll
   for (int i = 0; i < 2; i++) {
     const int e = 2 * tid + i;
-    cnt[i] = 0;
+    m[i] = 0;
     r0[i] = 0;
     if (e < n_slots) {
       r0[i] = offsets[e];
-      const int m = offsets[e + 1] - r0[i];
-      if (m > stream_max_rows) cnt[i] = (m + kTileM - 1) / kTileM;
+      m[i] = offsets[e + 1] - r0[i];
     }
   }
-  __syncthreads();  // scan_s may still be in use by the caller's own scan
-  scan_s[tid] = cnt[0] + cnt[1];
-  __syncthreads();
-  for (int d = 1; d < 1024; d <<= 1) {
-    const int v = (tid >= d) ? scan_s[tid - d] : 0;
+  // exclusive scan of v0 + v1 over the block; returns this thread's prefix, *total = sum over all
+  auto scan = [&](int v, int* total) {
+    __syncthreads();  // scan_s may still be in use (the caller's own scan, the previous list)
+    scan_s[tid] = v;
     __syncthreads();
-    scan_s[tid] += v;
-    __syncthreads();
-  }
-  int pos = scan_s[tid] - (cnt[0] + cnt[1]);  // exclusive prefix
+    for (int d = 1; d < 1024; d <<= 1) {
+      const int o = (tid >= d) ? scan_s[tid - d] : 0;
+      __syncthreads();
+      scan_s[tid] += o;
+      __syncthreads();
+    }
+    *total = scan_s[1023];
+    return scan_s[tid] - v;
+  };
+  // The tiled kernel's workgroups each take a whole compute unit: a handful of M tiles cannot fill
+  // the chip and keeps everything else off the units it holds.  Below min_tiles the experts that
+  // would be tiled join the row-group list (their weights are then read once per 64 rows).
+  bool tiled = false;
+  if (s.mt_expert) {
+    int cnt[2];
 #pragma unroll
-  for (int i = 0; i < 2; i++) {
-    for (int k = 0; k < cnt[i]; k++, pos++) {
-      if (pos < cap) {
-        mt_expert[pos] = 2 * tid + i;
-        mt_row0[pos] = r0[i] + k * kTileM;
-      }
-    }
+    for (int i = 0; i < 2; i++) cnt[i] = m[i] > stream_max_rows ? (m[i] + kTileM - 1) / kTileM : 0;
+    int total;
+    int pos = scan(cnt[0] + cnt[1], &total);
+    tiled = total >= s.min_tiles || !s.mid_expert;
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+      for (int k = 0; k < cnt[i] && tiled; k++, pos++)
+        if (pos < s.n_mt_max) {
+          s.mt_expert[pos] = 2 * tid + i;
+          s.mt_row0[pos] = r0[i] + k * kTileM;
+        }
+    if (tid == 0) *s.n_mtiles = tiled ? min(total, s.n_mt_max) : 0;
   }
-  if (tid == 1023) *n_mtiles = min(scan_s[1023], cap);
+  const int mid_max_rows = tiled ? stream_max_rows : 0x7fffffff;
+  if (s.mid_expert) {
+    int cnt[2];
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+      cnt[i] = (m[i] >= s.mid_min_rows && m[i] <= mid_max_rows) ? (m[i] + kMidRows - 1) / kMidRows : 0;
+    int total;
+    int pos = scan(cnt[0] + cnt[1], &total);
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+      for (int k = 0; k < cnt[i]; k++, pos++)
+        if (pos < s.mid_cap) {
+          s.mid_expert[pos] = 2 * tid + i;
+          s.mid_row0[pos] = r0[i] + k * kMidRows;
+        }
+    if (tid == 0) *s.n_mid = min(total, s.mid_cap);
+  }
 }
 
 }  // namespace dwdp

@@ -122,14 +122,13 @@ __device__ __forceinline__ void stream_mainloop(const uint8_t* const (&wt)[NT], 
 constexpr int kG1Waves = 4;
 constexpr int kG1T = 8 / kG1Waves;
 constexpr int kG1Threads = 64 * kG1Waves;
-__global__ __launch_bounds__(kG1Threads, 2) void gemm1_fp8_stream_kernel(
-    const dwdp_expert_ptrs* __restrict__ table, const int32_t* __restrict__ offsets, const int32_t* __restrict__ perm,
-    const uint8_t* __restrict__ xq, const float* __restrict__ xs, uint8_t* __restrict__ hq, float* __restrict__ hs,
-    int E, int T, int H, int I, int K, int max_rows) {
-  __shared__ float amax_s[kG1Waves][16];
+__device__ __forceinline__ void gemm1_fp8_stream_item(
+    int block, float (*amax_s)[16], const dwdp_expert_ptrs* __restrict__ table, const int32_t* __restrict__ offsets,
+    const int32_t* __restrict__ perm, const uint8_t* __restrict__ xq, const float* __restrict__ xs,
+    uint8_t* __restrict__ hq, float* __restrict__ hs, int E, int T, int H, int I, int K, int max_rows) {
   const int njb = I / 128;
-  const int e = blockIdx.x / njb;
-  const int jb = blockIdx.x - e * njb;
+  const int e = block / njb;
+  const int jb = block - e * njb;
   const int r0 = offsets[e];
   const int r1 = offsets[e + 1];
   if (r1 <= r0 || r1 - r0 > max_rows) return;  // no tokens: weights never touched; many: tiled kernel
@@ -246,14 +245,13 @@ __device__ __forceinline__ void g2_mma(const G2Frag& f, v4f (&acc)[kG2Tiles]) {
   }
 }
 
-__global__ __launch_bounds__(kStreamThreads, 2) void gemm2_fp8_stream_kernel(
+__device__ __forceinline__ void gemm2_fp8_stream_item(
+    int block, uint8_t* lds_x /* kG2ChunkKb * kTileBytes */, float* lds_sa /* kG2ChunkKb * 16 */,
     const dwdp_expert_ptrs* __restrict__ table, const int32_t* __restrict__ offsets, const uint8_t* __restrict__ hq,
     const float* __restrict__ hs, uint16_t* __restrict__ yp, int H, int I, int max_rows) {
-  __shared__ __attribute__((aligned(16))) uint8_t lds_x[kG2ChunkKb * kTileBytes];  // 32 KiB
-  __shared__ float lds_sa[kG2ChunkKb * 16];
   const int nnb = (H + kG2Rows - 1) / kG2Rows;
-  const int e = blockIdx.x / nnb;
-  const int nb = blockIdx.x - e * nnb;
+  const int e = block / nnb;
+  const int nb = block - e * nnb;
   const int r0 = offsets[e];
   const int r1 = offsets[e + 1];
   if (r1 <= r0 || r1 - r0 > max_rows) return;
@@ -346,20 +344,296 @@ __global__ __launch_bounds__(kStreamThreads, 2) void gemm2_fp8_stream_kernel(
   }
 }
 
-void launch_gemm1_fp8(const GemmArgs& a, int max_rows, const uint8_t* xq, const float* xs, uint8_t* hq, float* hs,
-                      hipStream_t stream) {
-  if (a.T <= 0) return;
-  dim3 grid(a.n_slots * (a.I / 128));
-  hipLaunchKernelGGL(gemm1_fp8_stream_kernel, grid, dim3(kG1Threads), 0, stream, a.table, a.offsets, a.perm, xq,
-                     xs, hq, hs, a.E, a.T, a.H, a.I, a.K, max_rows);
+// ------------------------------------------------------- experts with 17 .. max_rows rows
+// The same weight streams with several 16-token tiles per pass: a workgroup item is (row group
+// of up to kMidRows = 64 sorted rows of one expert, panel of 128 h columns or 128 output rows).
+// Every weight fragment in registers feeds kMidNB matrix instructions (one per token tile)
+// instead of one, so an expert with up to 64 rows is still read from HBM once and an expert
+// with more rows once per 64 -- without the whole-compute-unit workgroups of the LDS-tiled
+// kernel, which a short list of such experts cannot fill and which cannot share a compute unit
+// with anything else.  The token operand (the same for the four waves) is staged in LDS in
+// chunks of kMidKC K blocks, in the swizzled 16-row images of the one-tile GEMM-2 above; the
+// weight loads of the next K blocks stay in flight across a chunk boundary.
+constexpr int kMidNB = kMidRows / 16;                      // token tiles per pass (4)
+constexpr int kMidKC = 8;                                  // K blocks per staged chunk
+constexpr int kMidImgBytes = kMidKC * kMidNB * kTileBytes;  // 64 KiB
+constexpr int kMidLdsBytes = kMidImgBytes + kMidKC * kMidRows * 4 + kMidRows * 4 + 4 * kMidRows * 4;
+// K blocks per pipeline half of the multi-tile items: one in GEMM-1 (four weight tiles and 64
+// accumulators per wave leave registers for two K blocks of weights, 16 KiB per wave, in flight),
+// two in GEMM-2 (two weight tiles per wave)
+constexpr int kMidU1 = 1, kMidU2 = 2;
+static_assert(kMidKC % (2 * kMidU1) == 0 && kMidKC % (2 * kMidU2) == 0, "a chunk boundary falls on a pipeline round");
+
+template <int NT, int SG>
+struct WFrag {
+  v4i w[NT][2];
+  float sw[SG];
+};
+
+// wt[j]: this lane's address inside K block 0 of packed tile row j; tile j uses scale group j / (NT/SG)
+template <int NT, int SG>
+__device__ __forceinline__ void mid_load(WFrag<NT, SG>& f, const uint8_t* const (&wt)[NT],
+                                         const float* const (&swp)[SG], int kb) {
+#pragma unroll
+  for (int j = 0; j < NT; j++) {
+    const uint8_t* p = wt[j] + (size_t)kb * kTileBytes;
+    f.w[j][0] = __builtin_nontemporal_load((gv4i)p);
+    f.w[j][1] = __builtin_nontemporal_load((gv4i)(p + kTileBytes / 2));
+  }
+#pragma unroll
+  for (int g = 0; g < SG; g++) f.sw[g] = *(gf32)(swp[g] + kb);
 }
 
-void launch_gemm2_fp8(const GemmArgs& a, int max_rows, const uint8_t* hq, const float* hs, void* yp,
-                      hipStream_t stream) {
+// img: LDS image of this K block (kMidNB tiles of 16 rows x 128 bytes, swizzled); sa: its 64
+// activation scales; xo0/xo1: this lane's two chunk offsets inside a tile image
+template <int NT, int SG>
+__device__ __forceinline__ void mid_mma(const WFrag<NT, SG>& f, const uint8_t* img, const float* sa, int xo0, int xo1,
+                                        int lr, v4f (&acc)[NT][kMidNB]) {
+#pragma unroll
+  for (int tb = 0; tb < kMidNB; tb++) {
+    const v8i b = cat(*(const v4i*)(img + tb * kTileBytes + xo0), *(const v4i*)(img + tb * kTileBytes + xo1));
+    const float sat = sa[tb * 16 + lr];
+#pragma unroll
+    for (int j = 0; j < NT; j++) {
+      const v4f zero = {0.f, 0.f, 0.f, 0.f};
+      const v4f p = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(cat(f.w[j][0], f.w[j][1]), b, zero, 0, 0, 0, 0, 0, 0);
+      const float sj = sat * f.sw[j / (NT / SG)];
+#pragma unroll
+      for (int i = 0; i < 4; i++) acc[j][tb][i] = fmaf(p[i], sj, acc[j][tb][i]);
+    }
+  }
+}
+
+// G1: act/act_s = quantised x (rows gathered through perm), out = hq/hs; else act/act_s = hq/hs, out = yp.
+template <bool G1>
+__device__ __forceinline__ void gemm_fp8_mid_item(int block, uint8_t* lds, const dwdp_expert_ptrs* __restrict__ table,
+                                                  const int32_t* __restrict__ offsets, const int32_t* __restrict__ perm,
+                                                  const int32_t* __restrict__ mid_expert,
+                                                  const int32_t* __restrict__ mid_row0, const int32_t* __restrict__ n_mid,
+                                                  const uint8_t* __restrict__ act, const float* __restrict__ act_s,
+                                                  uint8_t* __restrict__ hq, float* __restrict__ hs,
+                                                  uint16_t* __restrict__ yp, int E, int T, int H, int I, int K) {
+  constexpr int NT = G1 ? 4 : 2;  // 16-row weight tiles per wave: G1 two gate + two up, GEMM-2 two
+  constexpr int SG = G1 ? 2 : 1;
+  const int n_panels = (G1 ? I : H) / 128;
+  const int g = block / n_panels;
+  const int panel = block - g * n_panels;
+  if (g >= *n_mid) return;
+  const int e = mid_expert[g];
+  const int r0 = mid_row0[g];
+  const int r1 = min(r0 + kMidRows, offsets[e + 1]);
+  uint8_t* img = lds;
+  float* lds_sa = (float*)(lds + kMidImgBytes);                  // [kMidKC][kMidRows]
+  int32_t* lds_row = (int32_t*)(lds_sa + kMidKC * kMidRows);     // [kMidRows] source row of every slot
+  float* amax_s = (float*)(lds_row + kMidRows);                  // [4 waves][kMidRows]
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63, lr = lane & 15, lq = lane >> 4;
+  const int Kdim = G1 ? H : I;
+  const int nkb = Kdim / 128;
+  if (tid < kMidRows) {
+    const int r = min(r0 + tid, r1 - 1);  // slots past the end repeat the last row and are not stored
+    lds_row[tid] = G1 ? ((e < E) ? perm[r] / K : r - T * K) : r;
+  }
+  const uint8_t* wbase = (const uint8_t*)(G1 ? table[e].w13 : table[e].w2);
+  const float* sbase = G1 ? table[e].s13 : table[e].s2;
+  const uint8_t* wt[NT];
+  const float* swp[SG];
+#pragma unroll
+  for (int j = 0; j < NT; j++) {
+    int row;  // first row of weight tile j
+    if (G1)
+      row = (j < 2 ? 0 : I) + panel * 128 + wave * 32 + (j & 1) * 16;
+    else
+      row = panel * 128 + wave * 32 + j * 16;
+    wt[j] = wbase + (size_t)(row / 16) * nkb * kTileBytes + lane * 16;
+  }
+  swp[0] = sbase + (size_t)panel * nkb;                                   // GEMM-1: the gate rows' scale block
+  if constexpr (G1) swp[1] = sbase + (size_t)(I / 128 + panel) * nkb;     // the up rows' scale block
+  const int xo0 = lr * 128 + (((2 * lq) ^ g2_swz(lr)) << 4);
+  const int xo1 = lr * 128 + (((2 * lq + 1) ^ g2_swz(lr)) << 4);
+
+  v4f acc[NT][kMidNB];
+#pragma unroll
+  for (int j = 0; j < NT; j++)
+#pragma unroll
+    for (int tb = 0; tb < kMidNB; tb++) acc[j][tb] = (v4f){0.f, 0.f, 0.f, 0.f};
+
+  // stage K blocks kc .. kc+nkc-1 of the group's rows (all threads; two barriers)
+  auto stage = [&](int kc) {
+    const int nkc = min(kMidKC, nkb - kc);
+    __syncthreads();  // the previous chunk's readers are done (and lds_row is written)
+    for (int p0 = 0; p0 < nkc * (kMidRows * 8); p0 += 8 * kStreamThreads) {
+      v4i v[8];
+#pragma unroll
+      for (int u = 0; u < 8; u++) {
+        const int pidx = min(p0 + u * kStreamThreads + tid, nkc * (kMidRows * 8) - 1);
+        const int kb = pidx >> 9, slot = (pidx >> 3) & (kMidRows - 1), c = pidx & 7;
+        v[u] = *(gv4i)(act + (size_t)lds_row[slot] * Kdim + (size_t)(kc + kb) * 128 + c * 16);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; u++) {
+        const int pidx = p0 + u * kStreamThreads + tid;
+        const int kb = pidx >> 9, slot = (pidx >> 3) & (kMidRows - 1), c = pidx & 7;
+        if (pidx < nkc * (kMidRows * 8))
+          *(v4i*)(img + kb * (kMidNB * kTileBytes) + (slot >> 4) * kTileBytes + (slot & 15) * 128 +
+                  ((c ^ g2_swz(slot & 15)) << 4)) = v[u];
+      }
+    }
+    for (int i = tid; i < nkc * kMidRows; i += kStreamThreads) {
+      const int kb = i / kMidRows, slot = i - kb * kMidRows;
+      lds_sa[i] = act_s[(size_t)lds_row[slot] * nkb + kc + kb];
+    }
+    __syncthreads();
+  };
+  auto mma = [&](const WFrag<NT, SG>& f, int kb) {
+    const int kl = kb & (kMidKC - 1);
+    mid_mma<NT, SG>(f, img + kl * (kMidNB * kTileBytes), lds_sa + kl * kMidRows, xo0, xo1, lr, acc);
+  };
+
+  __syncthreads();  // lds_row
+  constexpr int kUm = G1 ? kMidU1 : kMidU2;
+  constexpr int kStep = 2 * kUm;
+  const int nmain = (nkb / kStep) * kStep;
+  if (nmain > 0) {
+    WFrag<NT, SG> f0[kUm], f1[kUm];
+#pragma unroll
+    for (int u = 0; u < kUm; u++) mid_load<NT, SG>(f0[u], wt, swp, u);
+    for (int kb0 = 0; kb0 < nmain; kb0 += kStep) {
+      if ((kb0 & (kMidKC - 1)) == 0) stage(kb0);  // f0's loads stay in flight behind the staging
+#pragma unroll
+      for (int u = 0; u < kUm; u++) mid_load<NT, SG>(f1[u], wt, swp, kb0 + kUm + u);
+#pragma unroll
+      for (int u = 0; u < kUm; u++) mma(f0[u], kb0 + u);
+      if (kb0 + kStep < nmain) {
+#pragma unroll
+        for (int u = 0; u < kUm; u++) mid_load<NT, SG>(f0[u], wt, swp, kb0 + kStep + u);
+      }
+#pragma unroll
+      for (int u = 0; u < kUm; u++) mma(f1[u], kb0 + kUm + u);
+    }
+  }
+  for (int kb = nmain; kb < nkb; kb++) {
+    if ((kb & (kMidKC - 1)) == 0) stage(kb);
+    WFrag<NT, SG> f;
+    mid_load<NT, SG>(f, wt, swp, kb);
+    mma(f, kb);
+  }
+
+  if (G1) {
+    // tiles 0,1 = gate and 2,3 = up rows of h columns panel*128 + wave*32 + {0,16} + lq*4 + i
+    const int njb = I / 128;
+    float amax[kMidNB];
+#pragma unroll
+    for (int tb = 0; tb < kMidNB; tb++) {
+      float m = 0.f;
+#pragma unroll
+      for (int j = 0; j < 2; j++)
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+          const float gv = acc[j][tb][i], uv = acc[2 + j][tb][i];
+          const float v = gv / (1.f + __expf(-gv)) * uv;
+          acc[j][tb][i] = v;
+          m = fmaxf(m, fabsf(v));
+        }
+      m = fmaxf(m, __shfl_xor(m, 16));
+      m = fmaxf(m, __shfl_xor(m, 32));
+      if (lq == 0) amax_s[wave * kMidRows + tb * 16 + lr] = m;
+      amax[tb] = m;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int tb = 0; tb < kMidNB; tb++) {
+      float m = amax[tb];
+#pragma unroll
+      for (int w = 0; w < 4; w++) m = fmaxf(m, amax_s[w * kMidRows + tb * 16 + lr]);
+      const float scale = m > 0.f ? m / 448.f : 1.f;
+      const int r = r0 + tb * 16 + lr;
+      if (r < r1) {
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+          const uint32_t q = pack_fp8x4(acc[j][tb][0] / scale, acc[j][tb][1] / scale, acc[j][tb][2] / scale,
+                                        acc[j][tb][3] / scale);
+          *(uint32_t*)(hq + (size_t)r * I + panel * 128 + wave * 32 + j * 16 + lq * 4) = q;
+        }
+        if (wave == 0 && lq == 0) hs[(size_t)r * njb + panel] = scale;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int tb = 0; tb < kMidNB; tb++) {
+      const int r = r0 + tb * 16 + lr;
+      if (r < r1) {
+#pragma unroll
+        for (int j = 0; j < NT; j++) {
+          uint2 o;
+          o.x = (uint32_t)f32_to_bf16(acc[j][tb][0]) | ((uint32_t)f32_to_bf16(acc[j][tb][1]) << 16);
+          o.y = (uint32_t)f32_to_bf16(acc[j][tb][2]) | ((uint32_t)f32_to_bf16(acc[j][tb][3]) << 16);
+          *(uint2*)(yp + (size_t)r * H + panel * 128 + wave * 32 + j * 16 + lq * 4) = o;
+        }
+      }
+    }
+  }
+}
+
+// One launch per GEMM serves both streaming families: the first n_mid_blocks workgroups take the
+// row groups of the experts with 17 .. max_rows rows (longer items first), the others the
+// (expert, panel) items of the experts with 1 .. 16 rows.  With no row-group list
+// (n_mid_blocks = 0) the one-tile items also walk larger experts, 16 rows at a time.
+__global__ __launch_bounds__(kStreamThreads, 2) void gemm1_fp8_stream_kernel(
+    const dwdp_expert_ptrs* __restrict__ table, const int32_t* __restrict__ offsets, const int32_t* __restrict__ perm,
+    const int32_t* __restrict__ mid_expert, const int32_t* __restrict__ mid_row0, const int32_t* __restrict__ n_mid,
+    int n_mid_blocks, const uint8_t* __restrict__ xq, const float* __restrict__ xs, uint8_t* __restrict__ hq,
+    float* __restrict__ hs, int E, int T, int H, int I, int K, int max_rows) {
+  __shared__ __attribute__((aligned(16))) uint8_t lds[kMidLdsBytes];
+  if ((int)blockIdx.x < n_mid_blocks)
+    gemm_fp8_mid_item<true>(blockIdx.x, lds, table, offsets, perm, mid_expert, mid_row0, n_mid, xq, xs, hq, hs, nullptr,
+                            E, T, H, I, K);
+  else
+    gemm1_fp8_stream_item(blockIdx.x - n_mid_blocks, (float(*)[16])lds, table, offsets, perm, xq, xs, hq, hs, E, T, H, I,
+                          K, max_rows);
+}
+
+__global__ __launch_bounds__(kStreamThreads, 2) void gemm2_fp8_stream_kernel(
+    const dwdp_expert_ptrs* __restrict__ table, const int32_t* __restrict__ offsets,
+    const int32_t* __restrict__ mid_expert, const int32_t* __restrict__ mid_row0, const int32_t* __restrict__ n_mid,
+    int n_mid_blocks, const uint8_t* __restrict__ hq, const float* __restrict__ hs, uint16_t* __restrict__ yp, int E,
+    int T, int H, int I, int K, int max_rows) {
+  __shared__ __attribute__((aligned(16))) uint8_t lds[kMidLdsBytes];
+  static_assert(kMidLdsBytes >= kG2ChunkKb * kTileBytes + kG2ChunkKb * 16 * 4, "the one-tile item's staging fits");
+  if ((int)blockIdx.x < n_mid_blocks)
+    gemm_fp8_mid_item<false>(blockIdx.x, lds, table, offsets, nullptr, mid_expert, mid_row0, n_mid, hq, hs, nullptr,
+                             nullptr, yp, E, T, H, I, K);
+  else
+    gemm2_fp8_stream_item(blockIdx.x - n_mid_blocks, lds, (float*)(lds + kG2ChunkKb * kTileBytes), table, offsets, hq,
+                          hs, yp, H, I, max_rows);
+}
+
+int mid_groups_cap(int rows, int n_slots, int mid_min_rows) {
+  // listed experts have at least mid_min_rows rows: at most rows / mid_min_rows of them, each
+  // adding at most one partial group to the rows / kMidRows full ones
+  const long by_rows = (long)rows / (mid_min_rows > 0 ? mid_min_rows : 1);
+  return rows / kMidRows + (int)(by_rows < n_slots ? by_rows : n_slots) + 1;
+}
+
+void launch_gemm1_fp8(const GemmArgs& a, int max_rows, const TileSched& ts, const uint8_t* xq, const float* xs,
+                      uint8_t* hq, float* hs, hipStream_t stream) {
   if (a.T <= 0) return;
-  dim3 grid(a.n_slots * ((a.H + kG2Rows - 1) / kG2Rows));
-  hipLaunchKernelGGL(gemm2_fp8_stream_kernel, grid, dim3(kStreamThreads), 0, stream, a.table, a.offsets, hq, hs,
-                     (uint16_t*)yp, a.H, a.I, max_rows);
+  const int n_mid_blocks = ts.mid_expert ? ts.mid_cap * (a.I / 128) : 0;
+  dim3 grid(n_mid_blocks + a.n_slots * (a.I / 128));
+  hipLaunchKernelGGL(gemm1_fp8_stream_kernel, grid, dim3(kStreamThreads), 0, stream, a.table, a.offsets, a.perm,
+                     ts.mid_expert, ts.mid_row0, ts.n_mid, n_mid_blocks, xq, xs, hq, hs, a.E, a.T, a.H, a.I, a.K,
+                     ts.mid_expert ? (max_rows < 16 ? max_rows : 16) : max_rows);
+}
+
+void launch_gemm2_fp8(const GemmArgs& a, int max_rows, const TileSched& ts, const uint8_t* hq, const float* hs,
+                      void* yp, hipStream_t stream) {
+  if (a.T <= 0) return;
+  const int n_mid_blocks = ts.mid_expert ? ts.mid_cap * (a.H / 128) : 0;
+  dim3 grid(n_mid_blocks + a.n_slots * ((a.H + kG2Rows - 1) / kG2Rows));
+  hipLaunchKernelGGL(gemm2_fp8_stream_kernel, grid, dim3(kStreamThreads), 0, stream, a.table, a.offsets,
+                     ts.mid_expert, ts.mid_row0, ts.n_mid, n_mid_blocks, hq, hs, (uint16_t*)yp, a.E, a.T, a.H, a.I,
+                     a.K, ts.mid_expert ? (max_rows < 16 ? max_rows : 16) : max_rows);
 }
 
 // Row-major fp8 [rows, cols] -> tile-major.  Tile (tr, kb) = rows tr*16.., columns kb*128..

@@ -42,13 +42,29 @@
 // every wait becomes a wait for everything), so the weight scales of block kb+1 are loaded at
 // the end of block kb's multiply and waited for together with the vector-memory wait.
 //
-// Workgroups are numbered so that all weight panels of one M tile run on the same XCD back
-// to back and share the token rows in its L2: block b runs on XCD b % 8 and handles M tile
-// (b/8 / n_panels) * 8 + b % 8, panel (b/8) % n_panels.  With many M tiles (kPairMinTiles or
-// more) an XCD takes them in pairs of list neighbours, panel by panel -- (pair, panel 0, first),
-// (pair, panel 0, second), (pair, panel 1, first) ... -- the same 2 x 16 workgroups at a time,
-// but the further M tiles of an expert with many rows (neighbours in the list) then fetch a
-// weight panel while the XCD's L2 still holds it.
+// Scheduling: ONE persistent launch of at most one workgroup per compute unit computes both
+// grouped GEMMs of the listed experts.  Work items are (M tile, weight panel) pairs, first all of
+// GEMM-1 (gate/up + SwiGLU, 128 h columns per panel), then all of GEMM-2 (down, 256 output rows per
+// panel); a workgroup takes its next item with an atomic ticket.  There is one ticket queue per
+// XCD (the eight dies have private L2 caches): M tile m belongs to the queue of XCD m % 8 and its
+// panels are consecutive tickets, so the workgroups of one die work on the same M tile at the same
+// time and share its token rows in that die's L2; with many M tiles (kPairMinTiles or more) a
+// queue takes list neighbours in pairs, panel by panel -- (pair, panel 0, first), (pair, panel 0,
+// second), (pair, panel 1, first) ... -- so that the further M tiles of an expert with many rows
+// fetch a weight panel while the die's L2 still holds it.  A workgroup whose own queue is empty
+// takes tickets of the other dies' queues.  A GEMM-2 item reads the h rows of its M tile, which
+// the GEMM-1 items of that tile write: each finished GEMM-1 item adds one (release, device scope)
+// to the tile's counter and a GEMM-2 item waits (acquire) until the counter has reached the
+// number of GEMM-1 panels.  The wait ends: tickets of a queue are handed out in order, GEMM-1
+// items first, so when a workgroup holds a GEMM-2 ticket every GEMM-1 ticket of that queue is
+// already held by a workgroup that is running.  As a second line of defence the wait is bounded
+// (kSpinLimit polls); a workgroup that gives up raises the error word and goes on, so the grid
+// always drains.  Compared with one workgroup per item this launches no workgroup that only
+// exits (each needs a whole compute unit to start), has no partial last round, and keeps the
+// compute units the tiled chain holds from GEMM-1 through GEMM-2 while other kernels (the
+// weight-streaming chain, a prefetch copy) fill the rest of the chip.  `phase_mask` restricts a
+// launch to the items of one GEMM (1 or 2; then no waiting takes place: stream order separates
+// the launches); 3 is the fused launch.
 //
 // GEMM-1 (G1): wave w owns gate rows and up rows of 16 h columns of the panel (the 32 rows of
 // its A operand), epilogue silu(g)*u, per-token amax over the panel's 128 h columns (LDS, 8
@@ -104,13 +120,16 @@ __device__ __forceinline__ v8i cat8(v4i lo, v4i hi) { return __builtin_shuffleve
 __device__ __forceinline__ uint32_t lds_offset(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }
-__device__ __forceinline__ void dma16(const uint8_t* src_lane, uint32_t dst_wave_uniform) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst_wave_uniform), "v"(src_lane)
+// The source is a wave-uniform base (scalar register pair) plus a 32-bit per-lane byte offset.
+__device__ __forceinline__ void dma16(const uint8_t* base_uniform, uint32_t off_lane, uint32_t dst_wave_uniform) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst_wave_uniform), "v"(off_lane),
+               "s"(base_uniform)
                : "memory");
 }
 // 12 bytes per lane; lane l's bytes land at dst + l*16 (measured: the fourth dword of a slot is not written)
-__device__ __forceinline__ void dma12(const float* src_lane, uint32_t dst_wave_uniform) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx3 %1, off" ::"s"(dst_wave_uniform), "v"(src_lane)
+__device__ __forceinline__ void dma12(const float* base_uniform, uint32_t off_lane, uint32_t dst_wave_uniform) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx3 %1, %2" ::"s"(dst_wave_uniform), "v"(off_lane),
+               "s"(base_uniform)
                : "memory");
 }
 
@@ -134,52 +153,52 @@ struct AFrag {
   int s[2];
 };
 
+// LDS of a workgroup, declared once in the kernel and handed to the item functions (a function-local
+// __shared__ array in a template would be allocated once per instantiation).
+struct TileLds {
+  // Three token images, each its own array so that the compiler can tell a copy into one from
+  // the reads of another.
+  uint8_t* b0;
+  uint8_t* b1;
+  uint8_t* b2;
+  // activation scales of three consecutive K blocks per token slot (16-byte slots, the layout
+  // the 12-byte copy writes), double-buffered by block triple
+  float* sg0;
+  float* sg1;
+  int32_t* row;
+  uint8_t* epi;  // amax / store staging
+};
+
+// One work item: the kBM x (128 h columns | 256 output rows) tile (M tile starting at sorted row r0 of
+// expert e, panel `panel`).  G1: act/act_s = quantised x, writes hq/hs; otherwise act/act_s = hq/hs,
+// writes yp.  All threads of the workgroup call it with the same arguments; it starts and ends
+// with the workgroup's LDS free for reuse (a barrier separates it from what follows).
 // MX = false: FP8 e4m3 weights (packed 2 KiB tiles, fp32 scale per 128x128 block, applied by the
 // VALU scaling).  MX = true: MXFP4 weights (packed 1 KiB tiles of E2M1 codes, one E8M0 scale per
 // 32 along K, applied by the matrix instruction itself), FP8 activations as before.
 template <bool G1, bool MX>
-__global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
-    const dwdp_expert_ptrs* __restrict__ table, const int32_t* __restrict__ offsets, const int32_t* __restrict__ perm,
-    const int32_t* __restrict__ mt_expert, const int32_t* __restrict__ mt_row0, const int32_t* __restrict__ n_mtiles,
-    int n_panels, const uint8_t* __restrict__ act, const float* __restrict__ act_s, uint8_t* __restrict__ hq,
-    float* __restrict__ hs, uint16_t* __restrict__ yp, int E, int T, int H, int I, int K) {
-  // Three token images, each its own array so that the compiler can tell a copy into one
-  // from the reads of another.
-  __shared__ __attribute__((aligned(16))) uint8_t lds_b0[kLdsB];
-  __shared__ __attribute__((aligned(16))) uint8_t lds_b1[kLdsB];
-  __shared__ __attribute__((aligned(16))) uint8_t lds_b2[kLdsB];
-  // activation scales of three consecutive K blocks per token slot (16-byte slots, the layout
-  // the 12-byte copy writes), double-buffered by block triple
-  __shared__ __attribute__((aligned(16))) float lds_sg0[kSaLen * 4];
-  __shared__ __attribute__((aligned(16))) float lds_sg1[kSaLen * 4];
-  __shared__ int32_t lds_row[kSaLen];
-  __shared__ __attribute__((aligned(16))) uint8_t lds_epi[kEpiBytes];  // amax / store staging
-
-  const int xcd = blockIdx.x & 7;
-  const int s = blockIdx.x >> 3;
-  const int n_mt = *n_mtiles;
-  int m, panel;
-  if (n_mt >= kPairMinTiles) {
-    // two consecutive M tiles side by side on one XCD
-    const int pq = s / (2 * n_panels);
-    const int within = s - pq * (2 * n_panels);
-    panel = within >> 1;
-    m = (pq * 8 + xcd) * 2 + (within & 1);
-  } else {
-    const int mq = s / n_panels;
-    panel = s - mq * n_panels;
-    m = mq * 8 + xcd;
-  }
-  if (m >= n_mt) return;
-  // wave-uniform values go through readfirstlane so that everything derived from them
-  // (weight/scale pointers, tile counts) lives in scalar registers and is loaded with s_load
-  const int e = __builtin_amdgcn_readfirstlane(mt_expert[m]);
-  const int r0 = __builtin_amdgcn_readfirstlane(mt_row0[m]);
-  const int r_end = __builtin_amdgcn_readfirstlane(offsets[e + 1]);
+__device__ __forceinline__ void tile_item(const TileLds& L, const dwdp_expert_ptrs* __restrict__ table,
+                                          const int32_t* __restrict__ perm, int e, int r0, int r_end, int panel,
+                                          const uint8_t* __restrict__ act, const float* __restrict__ act_s,
+                                          uint8_t* __restrict__ hq, float* __restrict__ hs,
+                                          uint16_t* __restrict__ yp, int E, int T, int H, int I, int K) {
+  uint8_t* const lds_b0 = L.b0;
+  uint8_t* const lds_b1 = L.b1;
+  uint8_t* const lds_b2 = L.b2;
+  float* const lds_sg0 = L.sg0;
+  float* const lds_sg1 = L.sg1;
+  int32_t* const lds_row = L.row;
+  uint8_t* const lds_epi = L.epi;
   const int valid = min(kBM, r_end - r0);
   const int ntt = (valid + 31) >> 5;  // 32-token tiles that hold rows of the expert
 
-  const int tid = threadIdx.x;
+  // Everything below is recomputed per item on purpose.  The thread index and the sizes pass
+  // through empty asm statements so that the compiler cannot hoist the (many) lane offsets and
+  // addresses derived from them out of the scheduler's loop, where the hoisted values of both
+  // GEMMs' item functions would stay live across every item and push the K loops into spilling.
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  asm volatile("" : "+s"(H), "+s"(I), "+s"(K), "+s"(T), "+s"(E));
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: pointers derived from it stay in SGPRs
   const int lane = tid & 63;
   const int ln = lane & 31;  // the weight row (A operand) and the token (B operand) this lane feeds
@@ -280,9 +299,9 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
     const int kb = min(pos, nkb - 1);
     if (op < kBP) {
       const int c = min(wave + kTileWaves * op, kBPieces - 1);
-      dma16(act + (b_src[op] + (uint32_t)kb * 128), img_off[img] + c * 1024);
+      dma16(act, b_src[op] + (uint32_t)kb * 128, img_off[img] + c * 1024);
     } else if (op == kBP) {
-      dma12(act_s + (sa_src + (uint32_t)kb), sg_off[(pos / 3) & 1]);
+      dma12(act_s, (sa_src + (uint32_t)kb) * 4, sg_off[(pos / 3) & 1]);
     } else {
       const int w = op - kBP - 1;  // FP8: 0..3 = (c, half); MXFP4: codes of half 0, half 1, scales of half 0, half 1
       if (!MX) {
@@ -556,6 +575,152 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_fp8_tile_kernel(
   }
 }
 
+// ---------------------------------------------------------------- persistent scheduler
+
+constexpr int kSpinLimit = 1 << 22;  // polls (of about 640 cycles) a GEMM-2 item waits for its GEMM-1 items
+
+// Layout of the scheduler's words (TileSched::sync), all zeroed by the kernel that builds the list:
+//   [0, 8)   ticket queues of the fused or the GEMM-1-only launch, one per XCD
+//   [8, 16)  ticket queues of the GEMM-2-only launch
+//   [16]     error word: a bounded wait gave up
+//   [kSyncDone + m] finished GEMM-1 items of M tile m
+static_assert(kTileSyncDone == 32, "layout documented above");
+
+// Ticket t of queue v -> item.  Returns 0 when the queue is exhausted, 1 for an item (phase 1 or
+// 2 in *phase), 2 for a ticket that names no M tile (padding of the last group) and is skipped.
+__device__ __forceinline__ int decode_ticket(int t, int v, int n_mt, int p1, int p2, int phase_mask, int* phase, int* m,
+                                             int* panel) {
+  const bool pairs = n_mt >= kPairMinTiles;
+  const int tiles = pairs ? 2 * ((n_mt + 15) / 16) : (n_mt + 7) / 8;  // M tile places of one queue
+  const int n1 = (phase_mask & 1) ? tiles * p1 : 0;
+  const int n2 = (phase_mask & 2) ? tiles * p2 : 0;
+  if (t >= n1 + n2) return 0;
+  const int ph = t < n1 ? 1 : 2;
+  const int i = ph == 1 ? t : t - n1;
+  const int np = ph == 1 ? p1 : p2;
+  int mm;
+  if (pairs) {
+    const int pq = i / (2 * np), within = i - pq * (2 * np);
+    *panel = within >> 1;
+    mm = (pq * 8 + v) * 2 + (within & 1);
+  } else {
+    const int mq = i / np;
+    *panel = i - mq * np;
+    mm = mq * 8 + v;
+  }
+  *phase = ph;
+  *m = mm;
+  return mm < n_mt ? 1 : 2;
+}
+
+template <bool MX>
+__global__ __launch_bounds__(kTileThreads, 1) void gemm_tile_persistent_kernel(
+    const dwdp_expert_ptrs* __restrict__ table, const int32_t* __restrict__ offsets, const int32_t* __restrict__ perm,
+    const int32_t* __restrict__ mt_expert, const int32_t* __restrict__ mt_row0, const int32_t* __restrict__ n_mtiles,
+    int32_t* __restrict__ sync, int phase_mask, const uint8_t* __restrict__ xq, const float* __restrict__ xs,
+    uint8_t* __restrict__ hq, float* __restrict__ hs, uint16_t* __restrict__ yp, int E, int T, int H, int I, int K) {
+  __shared__ __attribute__((aligned(16))) uint8_t lds_b0[kLdsB];
+  __shared__ __attribute__((aligned(16))) uint8_t lds_b1[kLdsB];
+  __shared__ __attribute__((aligned(16))) uint8_t lds_b2[kLdsB];
+  __shared__ __attribute__((aligned(16))) float lds_sg0[kSaLen * 4];
+  __shared__ __attribute__((aligned(16))) float lds_sg1[kSaLen * 4];
+  __shared__ int32_t lds_row[kSaLen];
+  __shared__ __attribute__((aligned(16))) uint8_t lds_epi[kEpiBytes];
+  __shared__ int32_t lds_item[4];  // phase (0 = no more work), M tile, panel
+  const TileLds L{lds_b0, lds_b1, lds_b2, lds_sg0, lds_sg1, lds_row, lds_epi};
+
+  const int xcd = blockIdx.x & 7;  // workgroups are dealt to the dies in turn
+  const int n_mt = *n_mtiles;
+  const int p1 = I / 128, p2 = (H + 255) / 256;
+  int32_t* tickets = sync + (phase_mask == 2 ? 8 : 0);
+  int32_t* done1 = sync + kTileSyncDone;
+  int first_victim = 0;  // queues before this one (counted from the own) are known to be empty
+
+  for (;;) {
+    if (threadIdx.x == 0) {
+      int phase = 0, m = 0, panel = 0;
+      while (first_victim < 8) {
+        const int v = (xcd + first_victim) & 7;
+        const int t = atomicAdd(&tickets[v], 1);
+        const int r = decode_ticket(t, v, n_mt, p1, p2, phase_mask, &phase, &m, &panel);
+        if (r == 1) break;
+        phase = 0;
+        if (r == 0) first_victim++;
+      }
+      if (phase == 2 && phase_mask == 3) {
+        // the h rows of this M tile are complete once all its GEMM-1 items have signalled
+        int spins = 0;
+        while (__hip_atomic_load(&done1[m], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < p1) {
+          __builtin_amdgcn_s_sleep(10);
+          if (++spins > kSpinLimit) {
+            atomicExch(&sync[kTileSyncError], 1);
+            break;
+          }
+        }
+      }
+      lds_item[0] = phase;
+      lds_item[1] = m;
+      lds_item[2] = panel;
+    }
+    __syncthreads();
+    const int phase = __builtin_amdgcn_readfirstlane(lds_item[0]);
+    const int m = __builtin_amdgcn_readfirstlane(lds_item[1]);
+    const int panel = __builtin_amdgcn_readfirstlane(lds_item[2]);
+    if (phase == 0) return;
+    // every wave orders its reads of h behind the counter it (through thread 0) has seen
+    if (phase == 2 && phase_mask == 3) __atomic_thread_fence(__ATOMIC_ACQUIRE);
+    // wave-uniform values go through readfirstlane so that everything derived from them
+    // (weight/scale pointers, tile counts) lives in scalar registers and is loaded with s_load
+    const int e = __builtin_amdgcn_readfirstlane(mt_expert[m]);
+    const int r0 = __builtin_amdgcn_readfirstlane(mt_row0[m]);
+    const int r_end = __builtin_amdgcn_readfirstlane(offsets[e + 1]);
+    if (phase == 1) {
+      tile_item<true, MX>(L, table, perm, e, r0, r_end, panel, xq, xs, hq, hs, nullptr, E, T, H, I, K);
+      // all of this workgroup's h stores are ordered before the signal: barrier (workgroup
+      // scope), then one release at device scope
+      __syncthreads();
+      if (threadIdx.x == 0) __hip_atomic_fetch_add(&done1[m], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+      tile_item<false, MX>(L, table, perm, e, r0, r_end, panel, hq, hs, nullptr, nullptr, yp, E, T, H, I, K);
+      __syncthreads();  // lds_item and the epilogue staging are rewritten by the next round
+    }
+  }
+}
+
+// One workgroup per (M tile, panel) item of ONE GEMM, numbered so that all weight panels of an M
+// tile run on the same XCD back to back and share the token rows in its L2: block b runs on XCD
+// b % 8 and handles M tile (b/8 / n_panels) * 8 + b % 8, panel (b/8) % n_panels; with
+// kPairMinTiles or more M tiles an XCD takes list neighbours in pairs, panel by panel (the same
+// order as the persistent kernel's ticket queues).  The grid is sized from a host-side upper
+// bound of the list; surplus workgroups exit.  Unlike the persistent launch, finished
+// workgroups give their compute unit back, so a concurrently running kernel (the weight-streaming
+// chain) gets compute units whenever this one has fewer items left than the chip has units.
+template <bool G1, bool MX>
+__global__ __launch_bounds__(kTileThreads, 1) void gemm_tile_item_kernel(
+    const dwdp_expert_ptrs* __restrict__ table, const int32_t* __restrict__ offsets, const int32_t* __restrict__ perm,
+    const int32_t* __restrict__ mt_expert, const int32_t* __restrict__ mt_row0, const int32_t* __restrict__ n_mtiles,
+    int n_panels, const uint8_t* __restrict__ act, const float* __restrict__ act_s, uint8_t* __restrict__ hq,
+    float* __restrict__ hs, uint16_t* __restrict__ yp, int E, int T, int H, int I, int K) {
+  __shared__ __attribute__((aligned(16))) uint8_t lds_b0[kLdsB];
+  __shared__ __attribute__((aligned(16))) uint8_t lds_b1[kLdsB];
+  __shared__ __attribute__((aligned(16))) uint8_t lds_b2[kLdsB];
+  __shared__ __attribute__((aligned(16))) float lds_sg0[kSaLen * 4];
+  __shared__ __attribute__((aligned(16))) float lds_sg1[kSaLen * 4];
+  __shared__ int32_t lds_row[kSaLen];
+  __shared__ __attribute__((aligned(16))) uint8_t lds_epi[kEpiBytes];
+  const TileLds L{lds_b0, lds_b1, lds_b2, lds_sg0, lds_sg1, lds_row, lds_epi};
+  int phase, m, panel;
+  const int n_mt = *n_mtiles;
+  // the numbering of the persistent kernel's queues: this workgroup is ticket blockIdx / 8 of queue blockIdx % 8
+  if (decode_ticket(blockIdx.x >> 3, blockIdx.x & 7, n_mt, G1 ? n_panels : 0, G1 ? 0 : n_panels, G1 ? 1 : 2, &phase, &m,
+                    &panel) != 1)
+    return;
+  const int e = __builtin_amdgcn_readfirstlane(mt_expert[m]);
+  const int r0 = __builtin_amdgcn_readfirstlane(mt_row0[m]);
+  const int r_end = __builtin_amdgcn_readfirstlane(offsets[e + 1]);
+  tile_item<G1, MX>(L, table, perm, e, r0, r_end, panel, act, act_s, hq, hs, yp, E, T, H, I, K);
+}
+
 int tile_mtiles_cap(int rows, int n_slots, int stream_max_rows) {
   // listed experts have more than stream_max_rows rows: at most rows / (stream_max_rows+1) of
   // them, each adding at most one partial tile to the rows / kBM full ones
@@ -563,26 +728,40 @@ int tile_mtiles_cap(int rows, int n_slots, int stream_max_rows) {
   return rows / kBM + (int)(by_rows < n_slots ? by_rows : n_slots) + 1;
 }
 
-// covers both numberings of the kernel: M tiles rounded up to whole pairs on all 8 XCDs
-static int tile_grid(int n_mt_max, int n_panels) { return 16 * ((n_mt_max + 15) / 16) * n_panels; }
+int tile_sync_words(int mt_cap) { return kTileSyncDone + mt_cap; }
 
-void launch_gemm1_fp8_tile(const GemmArgs& a, const TileSched& ts, bool mxfp4, const uint8_t* xq, const float* xs,
-                           uint8_t* hq, float* hs, hipStream_t stream) {
-  const int n_panels = a.I / 128;
-  const int grid = tile_grid(ts.n_mt_max, n_panels);
-  auto kern = mxfp4 ? gemm_fp8_tile_kernel<true, true> : gemm_fp8_tile_kernel<true, false>;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kTileThreads), 0, stream, a.table, a.offsets, a.perm, ts.mt_expert,
-                     ts.mt_row0, ts.n_mtiles, n_panels, xq, xs, hq, hs, (uint16_t*)nullptr, a.E, a.T, a.H, a.I, a.K);
-}
-
-void launch_gemm2_fp8_tile(const GemmArgs& a, const TileSched& ts, bool mxfp4, const uint8_t* hq, const float* hs,
-                           void* yp, hipStream_t stream) {
-  const int n_panels = (a.H + 255) / 256;
-  const int grid = tile_grid(ts.n_mt_max, n_panels);
-  auto kern = mxfp4 ? gemm_fp8_tile_kernel<false, true> : gemm_fp8_tile_kernel<false, false>;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kTileThreads), 0, stream, a.table, a.offsets, a.perm, ts.mt_expert,
-                     ts.mt_row0, ts.n_mtiles, n_panels, hq, hs, (uint8_t*)nullptr, (float*)nullptr, (uint16_t*)yp, a.E,
-                     a.T, a.H, a.I, a.K);
+// schedule 0: one workgroup per item (phase_mask 1 or 2 only); 1: the persistent kernel.
+// phase_mask 3 (persistent only): both GEMMs in one launch; 1 / 2: one of them (two launches in stream order).
+void launch_gemm_fp8_tile(const GemmArgs& a, const TileSched& ts, bool mxfp4, int schedule, int phase_mask,
+                          const uint8_t* xq, const float* xs, uint8_t* hq, float* hs, void* yp, int n_cus,
+                          hipStream_t stream) {
+  const int p1 = a.I / 128, p2 = (a.H + 255) / 256;
+  if (schedule == 0) {
+    const bool g1 = phase_mask == 1;
+    const int n_panels = g1 ? p1 : p2;
+    // covers both numberings of the kernel: M tiles rounded up to whole pairs on all 8 XCDs
+    const int grid = 16 * ((ts.n_mt_max + 15) / 16) * n_panels;
+    if (g1) {
+      auto kern = mxfp4 ? gemm_tile_item_kernel<true, true> : gemm_tile_item_kernel<true, false>;
+      hipLaunchKernelGGL(kern, dim3(grid), dim3(kTileThreads), 0, stream, a.table, a.offsets, a.perm, ts.mt_expert,
+                         ts.mt_row0, ts.n_mtiles, n_panels, xq, xs, hq, hs, (uint16_t*)nullptr, a.E, a.T, a.H, a.I, a.K);
+    } else {
+      auto kern = mxfp4 ? gemm_tile_item_kernel<false, true> : gemm_tile_item_kernel<false, false>;
+      hipLaunchKernelGGL(kern, dim3(grid), dim3(kTileThreads), 0, stream, a.table, a.offsets, a.perm, ts.mt_expert,
+                         ts.mt_row0, ts.n_mtiles, n_panels, (const uint8_t*)hq, (const float*)hs, (uint8_t*)nullptr,
+                         (float*)nullptr, (uint16_t*)yp, a.E, a.T, a.H, a.I, a.K);
+    }
+    return;
+  }
+  const long items = (long)ts.n_mt_max * ((phase_mask & 1 ? p1 : 0) + (phase_mask & 2 ? p2 : 0));
+  // one workgroup per compute unit at most, in whole rounds over the 8 dies
+  long grid = items < n_cus ? items : n_cus;
+  grid = (grid + 7) / 8 * 8;
+  if (grid < 8) grid = 8;
+  auto kern = mxfp4 ? gemm_tile_persistent_kernel<true> : gemm_tile_persistent_kernel<false>;
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kTileThreads), 0, stream, a.table, a.offsets, a.perm,
+                     ts.mt_expert, ts.mt_row0, ts.n_mtiles, ts.sync, phase_mask, xq, xs, hq, hs, (uint16_t*)yp, a.E, a.T,
+                     a.H, a.I, a.K);
 }
 
 }  // namespace dwdp

@@ -242,10 +242,9 @@ __global__ __launch_bounds__(kPermThreads) void permute_single_kernel(const int3
     perm[r] = i;
     inv_perm[i] = r;
   }
-  if (list.mt_expert) {
+  if (list.mt_expert || list.mid_expert) {
     __syncthreads();  // offsets[] above were written by other threads of this workgroup
-    build_mtile_list_block(offsets, E + (has_shared ? 1 : 0), stream_max_rows, list.mt_expert, list.mt_row0,
-                           list.n_mtiles, list.n_mt_max, scan_s);
+    build_work_lists_block(offsets, E + (has_shared ? 1 : 0), stream_max_rows, list, scan_s);
   }
 }
 
@@ -280,10 +279,9 @@ __global__ __launch_bounds__(kPermThreads) void permute_scan_kernel(int32_t* __r
   }
   block_scan_offsets(run, E, scan_s, offsets);
   if (has_shared && threadIdx.x == 0) offsets[E + 1] = T * K + T;
-  if (list.mt_expert) {
+  if (list.mt_expert || list.mid_expert) {
     __syncthreads();
-    build_mtile_list_block(offsets, E + (has_shared ? 1 : 0), stream_max_rows, list.mt_expert, list.mt_row0,
-                           list.n_mtiles, list.n_mt_max, scan_s);
+    build_work_lists_block(offsets, E + (has_shared ? 1 : 0), stream_max_rows, list, scan_s);
   }
 }
 
@@ -315,7 +313,7 @@ __global__ void permute_empty_kernel(int32_t* offsets, int n) {
 void launch_permute(const int32_t* ids, int T, int E, int K, int has_shared, int32_t* chunk_counts, int32_t* offsets,
                     int32_t* perm, int32_t* inv_perm, const TileSched* list_in, int stream_max_rows,
                     hipStream_t stream) {
-  const TileSched list = list_in ? *list_in : TileSched{nullptr, nullptr, nullptr, 0};
+  const TileSched list = list_in ? *list_in : TileSched{};
   const int n_off = E + 1 + (has_shared ? 1 : 0);
   if (T <= 0) {
     hipLaunchKernelGGL(permute_empty_kernel, dim3((n_off + 255) / 256), dim3(256), 0, stream, offsets, n_off);

@@ -34,6 +34,23 @@ def tolerance(cfg) -> float:
     return 5e-3 if cfg.w_dtype == inputs.W_BF16 else 2e-2
 
 
+def row_tolerance(cfg) -> float:
+    """Bar for the per-token metric (max over tokens of max|d| / max|ref| inside the token's row).
+
+    bf16 weights: the global bar.  FP8 activations: the two sides accumulate h in different
+    orders, so an element of h that lies within rounding noise of an e4m3 rounding boundary may
+    get the neighbouring code on one side -- a step of 1/8 to 1/16 of that element.  Through the
+    down projection a flipped element j moves a row of the output by w2[:, j] * step, which
+    relative to the row's maximum is about 0.125 * |h_j| / (sqrt(I) * rms(h)): near 1 % at
+    I = 2048 when the largest element of the row flips, near 4 % at I = 128.  The whole-tensor
+    metric absorbs that; taken row by row the bar has to grow for narrow test layers:
+    2e-2 * max(1, sqrt(1024 / I))."""
+    t = tolerance(cfg)
+    if cfg.w_dtype == inputs.W_BF16:
+        return t
+    return t * max(1.0, (1024.0 / cfg.I) ** 0.5)
+
+
 def gpu_forward(ctx, cfg, x, logits, bias, table, layer=0):
     y = torch.empty(x.shape[0], cfg.H, dtype=torch.bfloat16, device=x.device)
     ctx.dwdp_moe_forward(layer, x, logits, bias, table, y)
