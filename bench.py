@@ -50,9 +50,16 @@ def parse():
     ap.add_argument("--tile-schedule", type=int, default=None, choices=[0, 1, 2],
                     help="override dwdp_set_tile_schedule: 0 = one workgroup per item, 1 = persistent launch per "
                          "GEMM, 2 = both tiled GEMMs in one persistent launch")
+    ap.add_argument("--tile-share", type=int, default=None,
+                    help="override dwdp_set_tile_share (persistent schedules: workgroups of the tiled launch "
+                         "when experts are streamed beside it)")
     ap.add_argument("--copy-engine", type=int, default=1, help="pipeline workload: 0 hipMemcpyAsync per slice, "
                                                                "1 copy-plan kernel")
-    ap.add_argument("--copy-wgs", type=int, default=512, help="pipeline workload: workgroups of the copy-plan kernel")
+    ap.add_argument("--copy-wgs", type=int, default=65535,
+                    help="pipeline workload: workgroups of the copy-plan kernel.  The default gives every 256 KiB "
+                         "unit of the plan a workgroup of its own: the copy then fills the chip, the GEMMs of the "
+                         "layer run after it, and each runs at its own best HBM rate (both are HBM-bound on one "
+                         "GPU).  A few hundred workgroups make the copy share the chip with the GEMMs instead")
     ap.add_argument("--weights", default="fp8", choices=["fp8", "mxfp4"],
                     help="expert weight format of the decode/prefill/skew workloads: block-scaled FP8 (the "
                          "headline configuration) or MXFP4 (FP4 codes with a power-of-two scale per 32)")
@@ -62,6 +69,10 @@ def parse():
     ap.add_argument("--pullers", type=int, default=1,
                     help="pipeline workload: with N > 1, time N contexts (stand-ins for N ranks) that pull the "
                          "same layer from the same source pool at once, over slice sizes and both copy engines")
+    ap.add_argument("--resident", type=int, default=64,
+                    help="pipeline workload: routed experts kept resident per layer (a DWDP group of N ranks keeps "
+                         "about 256 / N); the others are split evenly over --peers")
+    ap.add_argument("--peers", type=int, default=3, help="pipeline workload: peers the non-resident experts are pulled from")
     ap.add_argument("--merge-baseline", action="store_true",
                     help="pipeline workload: merge resident and staged experts into one contiguous image before "
                          "every layer (the naive split-weight baseline) instead of reading them in place")
@@ -238,6 +249,8 @@ def run_all(args):
         ctx.dwdp_set_stream_max_rows(args.stream_max_rows)
     if args.tile_schedule is not None:
         ctx.dwdp_set_tile_schedule(args.tile_schedule)
+    if args.tile_share is not None:
+        ctx.dwdp_set_tile_share(args.tile_share)
     smr = args.stream_max_rows if args.stream_max_rows is not None else binding.DEFAULT_STREAM_MAX_ROWS
     # layer 0 with its 192 non-resident experts read in place from the peer pool: every expert resident
     table = rig.layers.all_resident_table(0, dev)
@@ -276,6 +289,13 @@ def run_all(args):
         del leg_p, x_p, lg_p
     if "pipeline" in legs:
         out["pipeline"] = rig.measure(max(2, min(args.steps, 5)), max(1, min(args.warmup, 2)))
+        # the same pipeline with a copy kernel of 512 workgroups that stays resident beside the GEMMs:
+        # the configuration in which the copy's time span lies under the GEMMs' on the timeline
+        rig.set_copy_workgroups(512)
+        co = rig.measure(max(2, min(args.steps, 5)), 1)
+        out["pipeline_coresident_copy"] = {k: co[k] for k in (
+            "copy_engine", "ms_per_layer", "compute_alone_ms_per_layer", "copy_alone_ms_per_layer",
+            "exposed_copy_ms_per_layer", "hidden_frac", "overlap_frac_timeline", "hbm_frac")}
     if not args.no_cpu_baseline:
         from oracle import moe_oracle as mo
         n_tok = min(args.cpu_sample_tokens, cfg_d.T)
@@ -307,6 +327,8 @@ def run_single(args):
         ctx.dwdp_set_stream_max_rows(args.stream_max_rows)
     if args.tile_schedule is not None:
         ctx.dwdp_set_tile_schedule(args.tile_schedule)
+    if args.tile_share is not None:
+        ctx.dwdp_set_tile_share(args.tile_share)
     wp = ctx.pack_experts(w)          # one-off weight preparation, outside the timed region
     table = binding.expert_table(wp)
     torch.cuda.synchronize()

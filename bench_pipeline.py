@@ -51,8 +51,9 @@ def hidden_fraction(ms_per_layer: float, compute_alone_ms: float, copy_alone_ms:
 class PipelineRig:
     """Context, split-weight layer stack and per-layer inputs of the pipeline workload."""
 
-    def __init__(self, seed: int, T: int = None, T_max: int = None, copy_engine: int = 1, copy_wgs: int = 512,
-                 slice_bytes: int = 1 << 20, keep_logical_layer0: bool = False, dev=None):
+    def __init__(self, seed: int, T: int = None, T_max: int = None, copy_engine: int = 1, copy_wgs: int = 65535,
+                 slice_bytes: int = 1 << 20, keep_logical_layer0: bool = False, dev=None,
+                 n_resident: int = N_RESIDENT, n_peers: int = N_PEERS):
         self.dev = dev or torch.device("cuda:0")
         cfg = inputs.WORKLOADS["pipeline"]
         self.cfg = cfg if T is None else cfg.with_T(T)
@@ -62,7 +63,8 @@ class PipelineRig:
         self.ctx = binding.Context(self.cfg, n_layers=N_LAYERS, stream=self.stream,
                                    T_max=max(self.cfg.T, T_max or 0))
         self.ctx.dwdp_set_copy_engine(copy_engine, copy_wgs)
-        self.layers = pipeline.SplitWeightLayers(self.ctx, self.cfg, N_LAYERS, N_RESIDENT, N_PEERS, seed=seed,
+        self.n_resident, self.n_peers = n_resident, n_peers
+        self.layers = pipeline.SplitWeightLayers(self.ctx, self.cfg, N_LAYERS, n_resident, n_peers, seed=seed,
                                                  device=self.dev)
         if keep_logical_layer0:
             self.layers.logical[1:] = [None] * (N_LAYERS - 1)
@@ -78,8 +80,12 @@ class PipelineRig:
             self.ys.append(torch.empty(self.cfg.T, self.cfg.H, dtype=torch.bfloat16, device=self.dev))
         for l in range(N_LAYERS):      # device plans built here: no allocation inside the timed loops
             src, dst, nb = self.layers.prefetch_args(l)
-            self.ctx.dwdp_prepare_prefetch(l, src, dst, nb, N_PEERS, pipeline.N_PARAMS, slice_bytes)
+            self.ctx.dwdp_prepare_prefetch(l, src, dst, nb, n_peers, pipeline.N_PARAMS, slice_bytes)
         torch.cuda.synchronize()
+
+    def set_copy_workgroups(self, n: int):
+        self.copy_wgs = n
+        self.ctx.dwdp_set_copy_engine(self.engine, n)
 
     def close(self):
         self.ctx.close()
@@ -175,6 +181,7 @@ class PipelineRig:
         traffic = active * eb + 2 * pf_bytes       # weights read once by the GEMMs + the copy's read and write
         return {
             "T": cfg.T, "layers": N_LAYERS, "steps": steps, "slice_bytes": slice_bytes,
+            "resident_experts": self.n_resident, "peers": self.n_peers,
             "copy_engine": "copy-plan kernel, %d workgroups" % self.copy_wgs if self.engine == 1
             else "hipMemcpyAsync per slice",
             "split_weights": "merged into one contiguous image before every layer (naive baseline)" if merge
@@ -193,7 +200,8 @@ class PipelineRig:
 
 def run(args):
     rig = PipelineRig(args.seed, T=args.T, copy_engine=getattr(args, "copy_engine", 1),
-                      copy_wgs=getattr(args, "copy_wgs", 512), slice_bytes=getattr(args, "slice_mib", 1) << 20)
+                      copy_wgs=getattr(args, "copy_wgs", 65535), slice_bytes=getattr(args, "slice_mib", 1) << 20,
+                      n_resident=getattr(args, "resident", N_RESIDENT), n_peers=getattr(args, "peers", N_PEERS))
     if getattr(args, "stream_max_rows", None) is not None:
         rig.ctx.dwdp_set_stream_max_rows(args.stream_max_rows)
     m = rig.measure(args.steps, args.warmup, pad_ms=float(getattr(args, "window_pad_ms", 0.0) or 0.0),
@@ -203,7 +211,8 @@ def run(args):
         "metric": "moe_layer_tokens_per_s", "value": cfg.T / (m["ms_per_layer"] * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": m["ms_per_layer"] * N_LAYERS,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8_e4m3", "data": "synthetic",
-        "config": {"workload": "pipeline: 4 DeepSeek-R1-shaped MoE layers, 64 resident + 192 staged experts each",
+        "config": {"workload": "pipeline: 4 DeepSeek-R1-shaped MoE layers, %d resident + %d staged experts each"
+                               % (rig.n_resident, cfg.E - rig.n_resident),
                    "T": cfg.T, "layers": N_LAYERS, "slice_bytes": m["slice_bytes"],
                    "active_expert_slots": m["active_expert_slots"], "copy_engine": m["copy_engine"],
                    "split_weights": m["split_weights"], "prefetch_bytes_per_layer": m["prefetch_bytes_per_layer"]},
@@ -242,7 +251,7 @@ def run_pullers(args):
 
     def one_round(engine, slice_bytes, rotated, active):
         for c in ctxs:
-            c.dwdp_set_copy_engine(engine, getattr(args, "copy_wgs", 512))
+            c.dwdp_set_copy_engine(engine, min(getattr(args, "copy_wgs", 512), 512))
         torch.cuda.synchronize()
         e0 = torch.cuda.Event(enable_timing=True)
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(active)]

@@ -206,6 +206,13 @@ dwdp_status dwdp_set_stream_max_rows(dwdp_ctx* ctx, int32_t max_rows);
  */
 enum { DWDP_TILE_PER_ITEM = 0, DWDP_TILE_PERSISTENT = 1, DWDP_TILE_PERSISTENT_FUSED = 2 };
 dwdp_status dwdp_set_tile_schedule(dwdp_ctx* ctx, int32_t mode);
+/*
+ * Persistent schedules only: how many workgroups (= compute units; a multiple of 8, one round over
+ * the XCDs) a persistent tiled launch uses when at least 16 experts are streamed beside the tiled
+ * ones, so that the HBM-bound streaming chain has units of its own from the start.  0 = the
+ * default (13/16 of the chip).  With fewer streamed experts the launch uses every unit.
+ */
+dwdp_status dwdp_set_tile_share(dwdp_ctx* ctx, int32_t n_workgroups);
 
 /*
  * Weight preparation, done once when weights are loaded (on the owner of every expert,

@@ -64,6 +64,7 @@ def _load() -> C.CDLL:
                                        C.POINTER(dwdp_expert_ptrs)]
     lib.dwdp_set_stream_max_rows.argtypes = [vp, i32]
     lib.dwdp_set_tile_schedule.argtypes = [vp, i32]
+    lib.dwdp_set_tile_share.argtypes = [vp, i32]
     lib.dwdp_set_copy_engine.argtypes = [vp, i32, i32]
     lib.dwdp_pack_fp8_weight.argtypes = [vp, vp, vp, C.c_int64, C.c_int64]
     lib.dwdp_pack_mxfp4_weight.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int64]
@@ -218,6 +219,9 @@ class Context:
     def dwdp_set_tile_schedule(self, mode: int):
         """0: one workgroup per item; 1: persistent per GEMM; 2: persistent, both GEMMs in one launch."""
         self._check(lib.dwdp_set_tile_schedule(self.h, mode))
+
+    def dwdp_set_tile_share(self, n_workgroups: int):
+        self._check(lib.dwdp_set_tile_share(self.h, n_workgroups))
 
     def dwdp_pack_fp8_weight(self, src: torch.Tensor, dst: torch.Tensor):
         """src uint8 [..., rows, cols] row-major matrices -> dst (same shape) tile-major, matrix by matrix."""

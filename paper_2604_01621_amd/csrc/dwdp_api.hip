@@ -38,6 +38,7 @@ struct dwdp_ctx {
   int mt_cap = 0;
   int n_cus = 256;
   int tile_schedule = DWDP_TILE_PER_ITEM;
+  int tile_share_wgs = 0;  // 0: default share of a persistent tiled launch next to a streamed chain
   // prefetch engine: 0 = one hipMemcpyAsync per plan entry, 1 = one copy-plan kernel launch
   int copy_mode = 0;
   int copy_wgs = 256;
@@ -396,6 +397,9 @@ extern "C" dwdp_status dwdp_moe_forward(dwdp_ctx* ctx, int32_t layer, const void
     // fewer tiled GEMM-1 items than half the compute units: not worth whole-unit workgroups
     const int p1 = c.I / 128;
     ts.min_tiles = use_mid ? (ctx->n_cus / 2 + p1 - 1) / p1 : 0;
+    ts.wg_limit_full = ctx->n_cus;
+    ts.wg_limit_shared = ctx->tile_share_wgs > 0 ? ctx->tile_share_wgs : ctx->n_cus * 13 / 16 / 8 * 8;
+    ts.share_min_experts = 16;
   }
   if (use_mid) {
     ts.mid_expert = ctx->mid_expert;
@@ -726,6 +730,13 @@ extern "C" dwdp_status dwdp_set_stream_max_rows(dwdp_ctx* ctx, int32_t max_rows)
   if (!ctx) return DWDP_EINVAL;
   if (max_rows < 0) return fail(ctx, DWDP_EINVAL, "dwdp_set_stream_max_rows: negative");
   ctx->stream_max_rows = max_rows;
+  return DWDP_OK;
+}
+
+extern "C" dwdp_status dwdp_set_tile_share(dwdp_ctx* ctx, int32_t n_workgroups) {
+  if (!ctx) return DWDP_EINVAL;
+  if (n_workgroups < 0 || n_workgroups % 8) return fail(ctx, DWDP_EINVAL, "dwdp_set_tile_share: need a multiple of 8");
+  ctx->tile_share_wgs = n_workgroups;
   return DWDP_OK;
 }
 

@@ -44,6 +44,9 @@ struct TileSched {
                        // persistent tiled GEMM; zeroed by the kernel that builds the list
   int n_mt_max;        // host-side upper bound of the tiles listed by this call
   int sync_words;      // words of `sync` to zero
+  int wg_limit_full;   // persistent launches: workgroups that take work when (almost) nothing is streamed ...
+  int wg_limit_shared; // ... and when at least share_min_experts experts are streamed beside the tiled ones
+  int share_min_experts;
   int min_tiles;       // fewer M tiles than this (device-side count): none is listed, and when the row-group
                        // list is built those experts go there instead (see build_work_lists_block)
   // Row groups (up to kMidRows sorted rows of one expert) of the experts with mid_min_rows ..
@@ -58,6 +61,7 @@ constexpr int kMidRows = 64;        // rows of one group of the multi-tile strea
 // Upper bound of listed row groups for `rows` sorted rows over n_slots experts.
 int mid_groups_cap(int rows, int n_slots, int mid_min_rows);
 constexpr int kTileSyncError = 16;  // sync[16]: a bounded wait of the tiled GEMM gave up
+constexpr int kTileSyncLimit = 17;  // sync[17]: workgroups of a persistent launch that take work (the others exit)
 constexpr int kTileSyncDone = 32;   // sync[32 + m]: finished GEMM-1 items of M tile m
 // Upper bound of listed tiles when experts with more than stream_max_rows rows are listed.
 int tile_mtiles_cap(int rows, int n_slots, int stream_max_rows);
@@ -194,6 +198,7 @@ __device__ __forceinline__ void build_work_lists_block(const int32_t* offsets, i
   const int tid = threadIdx.x;
   // scheduler words of the persistent tiled GEMM (ticket queues, error word, per-tile counters)
   for (int i = tid; i < s.sync_words; i += 1024) s.sync[i] = 0;
+  __syncthreads();
   int m[2], r0[2];
 #pragma unroll
   for (int i = 0; i < 2; i++) {
@@ -240,6 +245,17 @@ __device__ __forceinline__ void build_work_lists_block(const int32_t* offsets, i
     if (tid == 0) *s.n_mtiles = tiled ? min(total, s.n_mt_max) : 0;
   }
   const int mid_max_rows = tiled ? stream_max_rows : 0x7fffffff;
+  if (s.mt_expert) {
+    // A persistent tiled launch holds its compute units to the end.  When a substantial number of
+    // experts is streamed beside it, it leaves part of the chip to that chain from the start
+    // (the streamed chain is bound by HBM and needs few units; the tiled one by unit time).
+    int n_str = 0;
+#pragma unroll
+    for (int i = 0; i < 2; i++) n_str += (m[i] > 0 && m[i] <= mid_max_rows) ? 1 : 0;
+    int total;
+    scan(n_str, &total);
+    if (tid == 0) s.sync[kTileSyncLimit] = total >= s.share_min_experts ? s.wg_limit_shared : s.wg_limit_full;
+  }
   if (s.mid_expert) {
     int cnt[2];
 #pragma unroll

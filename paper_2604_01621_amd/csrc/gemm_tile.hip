@@ -583,6 +583,7 @@ constexpr int kSpinLimit = 1 << 22;  // polls (of about 640 cycles) a GEMM-2 ite
 //   [0, 8)   ticket queues of the fused or the GEMM-1-only launch, one per XCD
 //   [8, 16)  ticket queues of the GEMM-2-only launch
 //   [16]     error word: a bounded wait gave up
+//   [17]     workgroups of a persistent launch that take work
 //   [kSyncDone + m] finished GEMM-1 items of M tile m
 static_assert(kTileSyncDone == 32, "layout documented above");
 
@@ -629,6 +630,9 @@ __global__ __launch_bounds__(kTileThreads, 1) void gemm_tile_persistent_kernel(
   __shared__ int32_t lds_item[4];  // phase (0 = no more work), M tile, panel
   const TileLds L{lds_b0, lds_b1, lds_b2, lds_sg0, lds_sg1, lds_row, lds_epi};
 
+  // the list builder bounds how many workgroups of a persistent launch take work (whole rounds over
+  // the dies); the others give their compute unit back at once
+  if ((int)blockIdx.x >= sync[kTileSyncLimit]) return;
   const int xcd = blockIdx.x & 7;  // workgroups are dealt to the dies in turn
   const int n_mt = *n_mtiles;
   const int p1 = I / 128, p2 = (H + 255) / 256;

@@ -21,8 +21,10 @@ void launch_quant_act(const void* x, int T, int H, uint8_t* xq, float* xs, hipSt
 // One block per token; each thread owns 8 consecutive columns per step.  The K routed rows
 // are added in slot order k = 0..K-1, then the shared expert's row: deterministic.
 // YP32 = false: yp is bf16 (FP8-weight path); true: yp is fp32 (bf16-weight path).
+constexpr int kCombineThreads = 128;  // H / 8 = 896 column chunks of the R1 shape are 7 whole steps of 128
+
 template <bool YP32>
-__global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ yp_,
+__global__ __launch_bounds__(kCombineThreads) void combine_kernel(const void* __restrict__ yp_,
                                                       const int32_t* __restrict__ inv_perm,
                                                       const float* __restrict__ topk_w, int T, int H, int K,
                                                       int has_shared, uint16_t* __restrict__ y) {
@@ -54,10 +56,11 @@ __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ y
         }
       }
     } else {
-      // rows in groups of kG: all loads of a group are issued before the first is used (the
-      // rows of a token lie far apart, one load at a time leaves the lane waiting on each);
-      // the adds keep the order k = 0..n-1.  Slots past n re-read the last row and are not added.
-      constexpr int kG = 5;
+      // rows in groups of kG (one group for top-8 routing with a shared expert): all loads of a
+      // group are issued before the first is used (the rows of a token lie far apart, one load
+      // at a time leaves the lane waiting on each); the adds keep the order k = 0..n-1.  Slots
+      // past n re-read the last row and are not added.
+      constexpr int kG = 9;
       for (int k0 = 0; k0 < n; k0 += kG) {
         v4i raw[kG];
 #pragma unroll
@@ -127,10 +130,10 @@ void launch_combine(const void* yp, bool yp_fp32, const int32_t* inv_perm, const
                     int has_shared, void* y, hipStream_t stream) {
   if (T <= 0) return;
   if (yp_fp32)
-    hipLaunchKernelGGL(combine_kernel<true>, dim3(T), dim3(256), 0, stream, yp, inv_perm, topk_w, T, H, K, has_shared,
-                       (uint16_t*)y);
+    hipLaunchKernelGGL(combine_kernel<true>, dim3(T), dim3(kCombineThreads), 0, stream, yp, inv_perm, topk_w, T, H, K,
+                       has_shared, (uint16_t*)y);
   else
-    hipLaunchKernelGGL(combine_kernel<false>, dim3(T), dim3(256), 0, stream, yp, inv_perm, topk_w, T, H, K,
+    hipLaunchKernelGGL(combine_kernel<false>, dim3(T), dim3(kCombineThreads), 0, stream, yp, inv_perm, topk_w, T, H, K,
                        has_shared, (uint16_t*)y);
 }
 
