@@ -112,6 +112,11 @@ void launch_gemm1_fp8(const GemmArgs& a, int max_rows, const TileSched& ts, cons
 // most n_cus workgroups that take items by atomic tickets -- phase_mask 3: GEMM-1 then GEMM-2 items
 // in one launch with device-side dependency counters; 1 or 2: one GEMM per launch.
 // mxfp4: the listed experts' weights are MXFP4 (launch_pack_mxfp4 layouts) instead of FP8.
+// Contract on the activation-scale arrays xs [T, H/128] and hs [rows, I/128]: the kernel copies a
+// row's scales three K blocks at a time, so when the number of K blocks is not a multiple of three it
+// reads up to two floats past the end of a row -- the next row's scales, or, after the last row, past
+// the array: both arrays must be followed by at least 8 readable bytes (the library's workspace
+// keeps 16 bytes of padding behind each).  What is read there is never used.
 void launch_gemm_fp8_tile(const GemmArgs& a, const TileSched& ts, bool mxfp4, int schedule, int phase_mask,
                           const uint8_t* xq, const float* xs, uint8_t* hq, float* hs, void* yp, int n_cus,
                           hipStream_t stream);
