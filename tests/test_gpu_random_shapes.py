@@ -1,5 +1,5 @@
 """Seeded random small layers against the oracle: shapes, routing set-ups, kernel-selection
-thresholds and bias kinds that the hand-picked cases do not enumerate (K loops of 1..6 blocks,
+thresholds, tile schedules and bias kinds that the hand-picked cases do not enumerate (K loops of 1..6 blocks,
 1..40 experts per kernel family, token counts around the 16-, 64- and 288-row tile edges)."""
 import random
 
@@ -22,17 +22,18 @@ def _case(rng):
     K = rng.randint(1, min(8, topk_group * per_group))
     return dict(T=rng.choice([1, 2, 3, 15, 16, 17, 31, 33, 64, 100, 290, 577, 700]), H=128 * rng.randint(1, 6),
                 I=128 * rng.randint(1, 5), E=E, K=K, n_group=n_group, topk_group=topk_group,
-                has_shared=rng.choice([0, 1])), rng.choice([0, 1, 5, 16, 16, 40, 1 << 30]), \
-        rng.choice(["none", "small", "zipf"]), rng.randint(0, 10 ** 6)
+                has_shared=rng.choice([0, 1])), rng.choice([0, 1, 5, 16, 16, 40, 64, 64, 100, 1 << 30]), \
+        rng.choice(["none", "small", "zipf"]), rng.randint(0, 10 ** 6), rng.choice([0, 0, 1, 2])
 
 
-@pytest.mark.parametrize("sweep_seed", [11, 12, 13])
+@pytest.mark.parametrize("sweep_seed", [11, 12, 13, 14])
 def test_random_small_layers(gpu_device, sweep_seed):
     from paper_2604_01621_amd import binding
     rng = random.Random(sweep_seed)
     for case in range(16):
-        shape, smr, bias_kind, seed = _case(rng)
-        print("random layer", sweep_seed, case, shape, "stream_max_rows", smr, "bias", bias_kind, "seed", seed, flush=True)
+        shape, smr, bias_kind, seed, schedule = _case(rng)
+        print("random layer", sweep_seed, case, shape, "stream_max_rows", smr, "bias", bias_kind, "seed", seed,
+              "tile schedule", schedule, flush=True)
         cfg = inputs.small_fp8_layer(**shape)
         x = inputs.make_activations(cfg, seed)
         logits = inputs.make_gate_logits(cfg, x, seed)
@@ -41,6 +42,7 @@ def test_random_small_layers(gpu_device, sweep_seed):
         wd = inputs.ExpertWeights(w.w13.cuda(), w.w2.cuda(), w.s13.cuda(), w.s2.cuda())
         ctx = binding.Context(cfg)
         ctx.dwdp_set_stream_max_rows(smr)
+        ctx.dwdp_set_tile_schedule(schedule)
         wp = ctx.pack_experts(wd)
         table = binding.expert_table(wp)
         y = torch.empty(cfg.T, cfg.H, dtype=torch.bfloat16, device="cuda")
