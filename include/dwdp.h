@@ -252,6 +252,9 @@ dwdp_status dwdp_pack_mxfp4_weight(dwdp_ctx* ctx, const void* src_codes, const v
  *     n_workgroups workgroups that walk the plan in order (entries cut into pieces of at
  *     most 256 KiB).  The slice order of the plan is kept, the slice size costs nothing,
  *     and n_workgroups bounds how many compute units the copy takes from the GEMMs.
+ *     With n_workgroups at or above the number of pieces every piece gets a workgroup of
+ *     its own, of 1024 threads (the shape with the best HBM rate); a smaller n_workgroups
+ *     gives that many 256-thread workgroups that walk the pieces round-robin.
  *     The device copy of a layer's plan is built on the first call with given arguments
  *     (one pinned-host and one device allocation, an asynchronous upload on the copy stream;
  *     no wait on any stream) and reused while the arguments stay the same.

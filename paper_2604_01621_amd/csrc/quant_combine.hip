@@ -91,7 +91,19 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const void* __
 // Executes a copy plan in one launch: unit u (dst, src, bytes) is copied by workgroup
 // u % gridDim.x, units in plan order, so the slice interleaving of the plan is kept while the
 // number of workgroups bounds how much of the chip the copy occupies.
-__global__ __launch_bounds__(256) void copy_plan_kernel(const CopyUnit* __restrict__ units, int n_units) {
+//
+// Shape of a workgroup, measured on an 8 GiB copy between two allocations (HBM traffic read +
+// written; a read-only kernel reaches 7.1 TB/s, a write-only one 6.1, hipMemcpyAsync 4.4-4.9):
+//   one workgroup per 256 KiB unit:  256 threads x 8 loads in flight 5.50 TB/s, 512 x 8 5.71,
+//                                    1024 x 4 5.84, 1024 x 8 6.05, 1024 x 16 5.94
+//   512 workgroups walking the plan: 256 threads 5.27 TB/s, 1024 threads 5.83
+// (plain instead of non-temporal loads or stores: 2-7 % less).  The larger the block a compute
+// unit reads before it turns to writing, the better the rate, so a launch that may take the
+// whole chip uses 1024 threads (128 KiB read, then written, per step); a launch bounded to fewer
+// workgroups than units is meant to run beside the GEMMs and keeps the light 256-thread shape,
+// which leaves the registers of a compute unit to them.
+template <int kThreads>
+__global__ __launch_bounds__(kThreads) void copy_plan_kernel(const CopyUnit* __restrict__ units, int n_units) {
   for (int u = blockIdx.x; u < n_units; u += gridDim.x) {
     const CopyUnit cu = units[u];
     const uint8_t* src = (const uint8_t*)cu.src;
@@ -102,28 +114,27 @@ __global__ __launch_bounds__(256) void copy_plan_kernel(const CopyUnit* __restri
       const v4i* s16 = (const v4i*)src;
       v4i* d16 = (v4i*)dst;
       size_t i = threadIdx.x;
-      // 16-byte loads in flight per lane.  Measured with 512 workgroups, 8.46 GB per launch, several
-      // processes (the rate depends on where the allocator placed the buffers): 8 in flight
-      // 2.74-2.96 ms, 6: 2.77-3.25 ms, 4: 3.18-3.29 ms
-      constexpr int kUn = 8;
-      for (; i + (kUn - 1) * 256 < n16; i += kUn * 256) {
+      constexpr int kUn = 8;  // 16-byte loads in flight per lane
+      for (; i + (size_t)(kUn - 1) * kThreads < n16; i += (size_t)kUn * kThreads) {
         v4i v[kUn];
 #pragma unroll
-        for (int j = 0; j < kUn; j++) v[j] = __builtin_nontemporal_load(s16 + i + j * 256);
+        for (int j = 0; j < kUn; j++) v[j] = __builtin_nontemporal_load(s16 + i + j * kThreads);
 #pragma unroll
-        for (int j = 0; j < kUn; j++) __builtin_nontemporal_store(v[j], d16 + i + j * 256);
+        for (int j = 0; j < kUn; j++) __builtin_nontemporal_store(v[j], d16 + i + j * kThreads);
       }
-      for (; i < n16; i += 256) d16[i] = s16[i];
+      for (; i < n16; i += kThreads) d16[i] = s16[i];
       done = n16 << 4;
     }
-    for (size_t i = done + threadIdx.x; i < cu.bytes; i += 256) dst[i] = src[i];
+    for (size_t i = done + threadIdx.x; i < cu.bytes; i += kThreads) dst[i] = src[i];
   }
 }
 
 void launch_copy_plan(const CopyUnit* units, int n_units, int n_workgroups, hipStream_t stream) {
   if (n_units <= 0) return;
-  const int g = n_units < n_workgroups ? n_units : n_workgroups;
-  hipLaunchKernelGGL(copy_plan_kernel, dim3(g), dim3(256), 0, stream, units, n_units);
+  if (n_workgroups >= n_units)
+    hipLaunchKernelGGL(copy_plan_kernel<1024>, dim3(n_units), dim3(1024), 0, stream, units, n_units);
+  else
+    hipLaunchKernelGGL(copy_plan_kernel<256>, dim3(n_workgroups), dim3(256), 0, stream, units, n_units);
 }
 
 void launch_combine(const void* yp, bool yp_fp32, const int32_t* inv_perm, const float* topk_w, int T, int H, int K,
