@@ -218,19 +218,29 @@ struct G2Frag {
 // wt[j]: wave-uniform base of packed tile row j; lane16 = lane * 16; xb0/xb1: this lane's two
 // chunk addresses inside K block 0 of the LDS image; kb counts from the chunk start, kbg is
 // the same block in the weight matrix.
-__device__ __forceinline__ void g2_load(G2Frag& f, const uint8_t* const (&wt)[kG2Tiles], uint32_t lane16,
-                                        const float* swp, const uint8_t* xb0, const uint8_t* xb1, const float* xsa,
-                                        int kb, int kbg) {
+__device__ __forceinline__ void g2_load_w(G2Frag& f, const uint8_t* const (&wt)[kG2Tiles], uint32_t lane16,
+                                          const float* swp, int kbg) {
 #pragma unroll
   for (int j = 0; j < kG2Tiles; j++) {
     const uint8_t* p = wt[j] + (size_t)kbg * kTileBytes + lane16;
     f.w[j][0] = __builtin_nontemporal_load((gv4i)p);
     f.w[j][1] = __builtin_nontemporal_load((gv4i)(p + kTileBytes / 2));
   }
+  f.sw = *(cf32)(swp + kbg);
+}
+
+__device__ __forceinline__ void g2_load_x(G2Frag& f, const uint8_t* xb0, const uint8_t* xb1, const float* xsa,
+                                          int kb) {
   f.x[0] = *(const v4i*)(xb0 + kb * kTileBytes);
   f.x[1] = *(const v4i*)(xb1 + kb * kTileBytes);
   f.sa = xsa[kb * 16];
-  f.sw = *(cf32)(swp + kbg);
+}
+
+__device__ __forceinline__ void g2_load(G2Frag& f, const uint8_t* const (&wt)[kG2Tiles], uint32_t lane16,
+                                        const float* swp, const uint8_t* xb0, const uint8_t* xb1, const float* xsa,
+                                        int kb, int kbg) {
+  g2_load_w(f, wt, lane16, swp, kbg);
+  g2_load_x(f, xb0, xb1, xsa, kb);
 }
 
 __device__ __forceinline__ void g2_mma(const G2Frag& f, v4f (&acc)[kG2Tiles]) {
@@ -281,27 +291,41 @@ __device__ __forceinline__ void gemm2_fp8_stream_item(
     for (int j = 0; j < kG2Tiles; j++) acc[j] = (v4f){0.f, 0.f, 0.f, 0.f};
     for (int kc = 0; kc < nkb; kc += kG2ChunkKb) {
       const int nkc = min(kG2ChunkKb, nkb - kc);
-      // stage rows rt..rt+15 (rows past the end repeat the last one), K blocks kc..kc+nkc-1
-      __syncthreads();  // the previous chunk's readers are done
-      for (int pidx = tid; pidx < nkc * 128; pidx += kStreamThreads) {
-        const int kb = pidx >> 7, row = (pidx >> 3) & 15, c = pidx & 7;
+      constexpr int kStep = 2 * kU2;
+      const int nmain = (nkc / kStep) * kStep;
+      // Stage rows rt..rt+15 (rows past the end repeat the last one), K blocks kc..kc+nkc-1.
+      // Order of issue: the chunk's h pieces (cache hits) into registers, then the first
+      // weight blocks (HBM); the LDS writes wait for the pieces only, so the weights' latency
+      // passes behind the staging and its barriers instead of after them.  The early weight
+      // loads are unconditional (block index clamped, a wave without rows reads tile row 0):
+      // a branch around them would make the wait before the LDS writes a wait for everything.
+      constexpr int kPieces = kG2ChunkKb * 128 / kStreamThreads;
+      v4i piece[kPieces];
+#pragma unroll
+      for (int it = 0; it < kPieces; it++) {
+        const int pidx = tid + it * kStreamThreads;
+        const int kb = min(pidx >> 7, nkc - 1), row = (pidx >> 3) & 15, c = pidx & 7;
         const int rc = min(rt + row, r1 - 1);
-        const v4i v = *(gv4i)(hq + (size_t)rc * I + (size_t)(kc + kb) * 128 + c * 16);
-        *(v4i*)(lds_x + kb * kTileBytes + row * 128 + ((c ^ g2_swz(row)) << 4)) = v;
+        piece[it] = *(gv4i)(hq + (size_t)rc * I + (size_t)(kc + kb) * 128 + c * 16);
       }
-      if (tid < nkc * 16) {
-        const int kb = tid >> 4, row = tid & 15;
-        lds_sa[kb * 16 + row] = hs[(size_t)min(rt + row, r1 - 1) * nkb + kc + kb];
+      const float piece_s = hs[(size_t)min(rt + (tid & 15), r1 - 1) * nkb + kc + min(tid >> 4, nkc - 1)];
+      G2Frag f0[kU2], f1[kU2];
+#pragma unroll
+      for (int u = 0; u < kU2; u++) g2_load_w(f0[u], wt, lane16, swp, min(kc + u, nkb - 1));
+      __syncthreads();  // the previous chunk's readers are done
+#pragma unroll
+      for (int it = 0; it < kPieces; it++) {
+        const int pidx = tid + it * kStreamThreads;
+        const int kb = pidx >> 7, row = (pidx >> 3) & 15, c = pidx & 7;
+        if (kb < nkc) *(v4i*)(lds_x + kb * kTileBytes + row * 128 + ((c ^ g2_swz(row)) << 4)) = piece[it];
       }
+      if (tid < nkc * 16) lds_sa[tid] = piece_s;
       __syncthreads();
       if (has_rows) {
         // two K blocks of weight loads in flight behind the MFMAs of the previous two
-        constexpr int kStep = 2 * kU2;
-        const int nmain = (nkc / kStep) * kStep;
         if (nmain > 0) {
-          G2Frag f0[kU2], f1[kU2];
 #pragma unroll
-          for (int u = 0; u < kU2; u++) g2_load(f0[u], wt, lane16, swp, xb0, xb1, xsa, u, kc + u);
+          for (int u = 0; u < kU2; u++) g2_load_x(f0[u], xb0, xb1, xsa, u);
           int kb0 = 0;
           for (; kb0 + kStep < nmain; kb0 += kStep) {
 #pragma unroll
