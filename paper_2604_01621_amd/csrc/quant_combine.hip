@@ -65,7 +65,9 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const void* __
         v4i raw[kG];
 #pragma unroll
         for (int j = 0; j < kG; j++)
-          raw[j] = *(const v4i*)((const uint16_t*)yp_ + (size_t)row_s[min(k0 + j, n - 1)] * H + c);
+          // non-temporal: every yp row is read once (0.26 -> 0.21 ms at 8192 tokens)
+          raw[j] = __builtin_nontemporal_load(
+              (const v4i*)((const uint16_t*)yp_ + (size_t)row_s[min(k0 + j, n - 1)] * H + c));
 #pragma unroll
         for (int j = 0; j < kG; j++) {
           if (k0 + j < n) {
