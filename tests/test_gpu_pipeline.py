@@ -170,6 +170,46 @@ def test_two_pullers_share_one_source(env, engine):
         ctx.dwdp_set_copy_engine(0)
 
 
+@pytest.mark.parametrize("engine,wgs", [(0, 0), (1, 1), (1, 7), (1, 65535)])
+@pytest.mark.parametrize("slice_bytes", [0, 1000, 262144 + 48])
+def test_copy_plan_moves_exact_bytes(gpu_device, engine, wgs, slice_bytes):
+    """The copy plan by itself (paper Section 4.3.2, Listing 1: every parameter of every peer,
+    slice by slice): odd lengths, addresses that are not multiples of 16, a parameter of zero
+    bytes; with one workgroup walking the whole plan, a few, and one per piece (the copy kernel's
+    two workgroup shapes).  Every destination equals its source byte for byte and the guard bytes
+    around each destination keep their pattern."""
+    from paper_2604_01621_amd import binding
+    print("copy plan engine", engine, "workgroups", wgs, "slice", slice_bytes, flush=True)
+    cfg = inputs.small_fp8_layer(T=8)
+    ctx = binding.Context(cfg, n_layers=2)
+    n_peers, n_params, guard = 3, 3, 256
+    sizes = [1_000_003, 0, 300_016]
+    g = torch.Generator().manual_seed(5)
+    srcs, dsts, src_ptrs, dst_ptrs = [], [], [], []
+    for q in range(n_peers):
+        for prm in range(n_params):
+            n = sizes[prm]
+            off_s, off_d = (q * 5 + prm) % 16, (q * 3 + prm * 7) % 16      # mixed alignments, some both 0 mod 16
+            if q == 0:
+                off_s = off_d = 0
+            sb = torch.randint(0, 256, (n + off_s + 16,), dtype=torch.uint8, generator=g).cuda()
+            db = torch.full((n + off_d + 2 * guard,), 0xA5, dtype=torch.uint8, device="cuda")
+            srcs.append((sb, off_s))
+            dsts.append((db, off_d))
+            src_ptrs.append(sb.data_ptr() + off_s)
+            dst_ptrs.append(db.data_ptr() + guard + off_d)
+    ctx.dwdp_set_copy_engine(engine, wgs if engine == 1 else 256)
+    ctx.dwdp_prefetch_layer(0, src_ptrs, dst_ptrs, sizes, n_peers, n_params, slice_bytes)
+    torch.cuda.current_stream().wait_stream(torch.cuda.ExternalStream(ctx.copy_stream_handle()))
+    torch.cuda.synchronize()
+    for i, ((sb, off_s), (db, off_d)) in enumerate(zip(srcs, dsts)):
+        n = sizes[i % n_params]
+        got = db.cpu().numpy()
+        np.testing.assert_array_equal(got[guard + off_d:guard + off_d + n], sb.cpu().numpy()[off_s:off_s + n], err_msg=str(i))
+        assert (got[:guard + off_d] == 0xA5).all() and (got[guard + off_d + n:] == 0xA5).all(), i
+    ctx.close()
+
+
 def test_prefetch_protocol_errors(env):
     binding, pipeline, cfg, ctx, layers, xs, lgs, bs = env
     print("pipeline protocol", flush=True)
